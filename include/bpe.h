@@ -1,0 +1,110 @@
+/* Byte-level BPE encoding of a batch of strings on one AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of BlockBPE (arXiv 2507.11941): given a merge table M (a list of token pairs, the
+ * row index being the pair's rank -- Algorithm 1, "Require") and a batch of byte strings, return for every
+ * string the token list T that Algorithm 1 ends with: start from the bytes, repeatedly replace the left-most
+ * occurrence of the lowest-rank adjacent pair by its merged token, stop when no adjacent pair is in M.
+ * Each string is encoded by one workgroup that loops over merge passes (section 4.2: look up pair ranks,
+ * workgroup minimum, mark, write; section 4.3: one block per string).
+ *
+ * Token ids: a byte b is token b (byte-level pre-tokenisation, section 4.1); the token created by row r is
+ * 256 + r.  Results are exact integers; there is nothing approximate in this interface.
+ *
+ * Every function returns one of the BPE_* codes below (0 = success); none throws, none keeps global state
+ * beyond a per-process cache of kernel attributes.  Pointers are marked HOST or DEVICE; all DEVICE pointers
+ * must belong to the device that was current when the table was built.
+ */
+#ifndef BPE_H_
+#define BPE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bpe_table bpe_table; /* opaque; owns its device memory */
+
+enum {
+  BPE_OK = 0,
+  BPE_EINVAL = -1,    /* null pointer, negative size, workspace too small, string longer than the maximum */
+  BPE_EBADMERGE = -2, /* a row uses an id that does not exist before that row (id >= 256 + row) or < 0 */
+  BPE_EDUPPAIR = -3,  /* the same (left,right) pair appears in two rows */
+  BPE_ENOMEM = -4,    /* host or device allocation failed */
+  BPE_EHIP = -5,      /* a HIP runtime call failed */
+  BPE_ETOOBIG = -6    /* more merges than the table format holds */
+};
+
+/* Largest string (bytes) bpe_encode_batch accepts, and largest number of merge rows a table holds. */
+#define BPE_MAX_STRING_BYTES 65536
+#define BPE_MAX_MERGES 1048318 /* ids stay below 2^20 - 1 */
+
+/* Build the GPU-resident merge table (the map R of Algorithm 1: pair -> rank, O(1) lookup; section 4.3's
+ * GPU hashmap).
+ *   merges   HOST, int32[n_merges][2]: row r = (left_id, right_id), rank r, merged id 256 + r.
+ *   n_merges >= 0.
+ *   out      HOST, receives the table handle (NULL on error).
+ *   bad_row  HOST, may be NULL; receives the first offending row on BPE_EBADMERGE / BPE_EDUPPAIR, else -1.
+ * Validates that every row's operands are in [0, 256 + r) -- the property of any trained table under which
+ * "apply every occurrence of the lowest rank per pass" equals Algorithm 1's one-at-a-time order -- and that
+ * no pair repeats.  The rows are copied; the caller keeps `merges`.  Allocates device memory on the current
+ * device and copies synchronously (this call is set-up, not hot path).
+ */
+int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, int32_t* bad_row);
+
+/* Release a table.  NULL is allowed.  The caller must have drained every stream that uses it. */
+void bpe_free_table(bpe_table* table);
+
+/* Number of merge rows of a table (0 for NULL). */
+int32_t bpe_table_n_merges(const bpe_table* table);
+
+/* Bytes of DEVICE workspace bpe_encode_batch needs for a batch of `batch` strings, `total_bytes` input
+ * bytes in all, longest string `max_len` bytes.  Returns 0 for invalid arguments (negative sizes, max_len
+ * above BPE_MAX_STRING_BYTES). */
+size_t bpe_workspace_bytes(int32_t batch, int64_t total_bytes, int32_t max_len);
+
+/* Encode a batch (Algorithm 1 per string; sections 4.2-4.3 for the parallel form).
+ *   table        from bpe_build_table; read-only here, so concurrent calls on different streams are safe
+ *                as long as each has its own workspace and outputs.
+ *   bytes        DEVICE, uint8[total_bytes]: the strings back to back.
+ *   offsets      DEVICE, int64[batch+1]: string i is bytes[offsets[i] .. offsets[i+1]); offsets[0] = 0,
+ *                non-decreasing, offsets[batch] = total_bytes.  Any byte sequence is valid input.
+ *   batch        number of strings, >= 0.
+ *   total_bytes  offsets[batch], passed by the host so that the call needs no device-to-host read.
+ *   max_len      an upper bound on the longest string, <= BPE_MAX_STRING_BYTES.  It selects which kernel
+ *                variants are launched.  A string longer than max_len makes the call's output undefined for
+ *                that string only if it also exceeds BPE_MAX_STRING_BYTES; otherwise it is still encoded
+ *                correctly as long as max_len was large enough to launch its variant -- pass the true
+ *                maximum.
+ *   out_ids      DEVICE, int32, capacity >= total_bytes ids (a string never has more tokens than bytes).
+ *   out_offsets  DEVICE, int64[batch+1].
+ *   workspace    DEVICE, >= bpe_workspace_bytes(batch, total_bytes, max_len) bytes, 256-byte aligned,
+ *                caller-owned; contents need not be initialised and are garbage afterwards.
+ *   stream       a hipStream_t passed as void* (NULL = the default stream).
+ * Only enqueues work on `stream`: no synchronisation, no allocation, no host reads of device data.  Once the
+ * stream has drained: out_offsets[0] = 0 and out_ids[out_offsets[i] .. out_offsets[i+1]) is the encoding of
+ * string i, dense and in batch order.  An empty string yields zero tokens.
+ * Errors (detected before anything is enqueued): BPE_EINVAL for null pointers with non-zero sizes, negative
+ * sizes, a short or misaligned workspace, or max_len out of range; BPE_EHIP if a launch fails.
+ */
+int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                     int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Duration in milliseconds of the encode kernels of the most recent bpe_encode_batch on this thread whose
+ * profiling was requested with bpe_set_profiling(1): HIP events recorded on the call's own stream around the
+ * per-string encode kernels only (not the binning, offset scan or packing kernels).  Synchronises on those
+ * events.  Returns a negative value if no such measurement exists. */
+float bpe_last_encode_kernel_ms(void);
+
+/* Turn the event recording above on (non-zero) or off (0, the default).  Per process. */
+void bpe_set_profiling(int enabled);
+
+/* Human-readable text for a BPE_* code. */
+const char* bpe_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPE_H_ */

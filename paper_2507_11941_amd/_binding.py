@@ -1,0 +1,139 @@
+"""ctypes binding of include/bpe.h: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbpe_hip.so")
+_lib = None
+
+MAX_STRING_BYTES = 65536
+
+
+class BpeError(RuntimeError):
+    def __init__(self, code: int, what: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{what}: {detail or code}")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libbpe_hip.so (built by ``paper_2507_11941_amd.build``).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2507_11941_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.bpe_build_table.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(i32)]
+    lib.bpe_build_table.restype = ctypes.c_int
+    lib.bpe_free_table.argtypes = [vp]
+    lib.bpe_free_table.restype = None
+    lib.bpe_table_n_merges.argtypes = [vp]
+    lib.bpe_table_n_merges.restype = i32
+    lib.bpe_workspace_bytes.argtypes = [i32, i64, i32]
+    lib.bpe_workspace_bytes.restype = ctypes.c_size_t
+    lib.bpe_encode_batch.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.bpe_encode_batch.restype = ctypes.c_int
+    lib.bpe_last_encode_kernel_ms.argtypes = []
+    lib.bpe_last_encode_kernel_ms.restype = ctypes.c_float
+    lib.bpe_set_profiling.argtypes = [ctypes.c_int]
+    lib.bpe_set_profiling.restype = None
+    lib.bpe_strerror.argtypes = [ctypes.c_int]
+    lib.bpe_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise BpeError(code, what, load_library().bpe_strerror(code).decode())
+
+
+class Table:
+    """Handle of a GPU-resident merge table (bpe_build_table / bpe_free_table)."""
+
+    def __init__(self, handle: int, n_merges: int):
+        self._h = handle
+        self.n_merges = n_merges
+
+    @property
+    def handle(self) -> int:
+        return self._h
+
+    def free(self):
+        if self._h:
+            load_library().bpe_free_table(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def build_table(merges) -> Table:
+    """merges: int32[n, 2] on the host; row index = rank, merged id = 256 + rank."""
+    lib = load_library()
+    m = np.ascontiguousarray(np.asarray(merges, dtype=np.int32).reshape(-1, 2))
+    handle = ctypes.c_void_p()
+    bad = ctypes.c_int32(-1)
+    code = lib.bpe_build_table(m.ctypes.data if len(m) else None, len(m), ctypes.byref(handle), ctypes.byref(bad))
+    if code != 0:
+        raise BpeError(code, "bpe_build_table", f"{lib.bpe_strerror(code).decode()} (row {bad.value})")
+    return Table(handle.value, len(m))
+
+
+def workspace_bytes(batch: int, total_bytes: int, max_len: int) -> int:
+    return int(load_library().bpe_workspace_bytes(batch, total_bytes, max_len))
+
+
+def encode_batch(table: Table, data, offsets, max_len: int, out_ids=None, out_offsets=None, workspace=None,
+                 stream=None):
+    """Enqueue one batch encode on ``stream`` (default: torch's current stream); returns
+    (out_ids int32[capacity], out_offsets int64[B+1]) device tensors.  ``data`` is a uint8 CUDA tensor with
+    the strings back to back, ``offsets`` an int64 CUDA tensor [B+1].  Nothing is synchronised."""
+    import torch
+
+    lib = load_library()
+    if not (data.is_cuda and offsets.is_cuda):
+        raise ValueError("encode_batch needs device tensors")
+    if data.dtype != torch.uint8 or offsets.dtype != torch.int64:
+        raise ValueError("data must be uint8 and offsets int64")
+    data = data.contiguous()
+    offsets = offsets.contiguous()
+    batch = offsets.numel() - 1
+    total = data.numel()
+    dev = data.device
+    if out_ids is None:
+        out_ids = torch.empty(max(total, 1), dtype=torch.int32, device=dev)
+    if out_offsets is None:
+        out_offsets = torch.empty(batch + 1, dtype=torch.int64, device=dev)
+    need = workspace_bytes(batch, total, max_len)
+    if need == 0:
+        raise BpeError(-1, "bpe_workspace_bytes", "invalid sizes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    code = lib.bpe_encode_batch(table.handle, data.data_ptr(), offsets.data_ptr(), batch, total, max_len,
+                                out_ids.data_ptr(), out_offsets.data_ptr(), workspace.data_ptr(),
+                                workspace.numel(), stream.cuda_stream)
+    _check(code, "bpe_encode_batch")
+    return out_ids, out_offsets
+
+
+def set_profiling(enabled: bool) -> None:
+    load_library().bpe_set_profiling(1 if enabled else 0)
+
+
+def last_encode_kernel_ms() -> float:
+    return float(load_library().bpe_last_encode_kernel_ms())

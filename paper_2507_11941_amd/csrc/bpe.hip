@@ -1,0 +1,336 @@
+// Host side of the C ABI declared in include/bpe.h: merge-table construction and the enqueue of one
+// batch encode.  Everything numeric happens in the kernels of encode_kernel.h / batch_kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/bpe.h"
+#include "batch_kernels.h"
+#include "encode_kernel.h"
+#include "table_format.h"
+
+using namespace bpe;
+
+struct bpe_table {
+  int device = 0;
+  int32_t n_merges = 0;
+  int log2_buckets = 0;
+  void* d_mem = nullptr;          // buckets followed by the 256 byte token words
+  size_t bucket_bytes = 0;
+};
+
+namespace {
+
+// ---- kernel variants ------------------------------------------------------------------------------
+// A variant is (waves per workgroup, positions per lane, tokens staged in HBM or LDS); it encodes
+// strings of up to 64 * waves * positions bytes.
+
+struct Variant {
+  int waves, depth;
+  bool staged;
+  int capacity;                   // bytes
+  size_t lds;
+  const void* fn;
+  void (*launch)(const EncodeParams&, int grid, hipStream_t);
+  int max_grid = 0;               // resident workgroups on the whole device (filled on first use)
+};
+
+template <int NW, int D, bool ST>
+void launch_variant(const EncodeParams& p, int grid, hipStream_t stream) {
+  constexpr size_t lds = encode_lds_bytes<NW, D, ST>();
+  encode_kernel<NW, D, ST><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
+}
+
+template <int NW, int D, bool ST>
+Variant make_variant() {
+  Variant v;
+  v.waves = NW;
+  v.depth = D;
+  v.staged = ST;
+  v.capacity = 64 * NW * D;
+  v.lds = encode_lds_bytes<NW, D, ST>();
+  v.fn = (const void*)&encode_kernel<NW, D, ST>;
+  v.launch = &launch_variant<NW, D, ST>;
+  return v;
+}
+
+// Default plan: <= 1 KiB one wave, <= 4 KiB four waves, <= 16 KiB sixteen waves (all LDS-resident),
+// <= 64 KiB sixteen waves with the token arrays staged in HBM.
+Variant g_variants[kMaxTiers] = {
+    make_variant<1, 16, false>(),
+    make_variant<4, 16, false>(),
+    make_variant<16, 16, false>(),
+    make_variant<16, 64, true>(),
+};
+std::once_flag g_variants_once;
+int g_variants_status = BPE_OK;
+int g_num_cus = 0;
+
+void init_variants() {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    g_variants_status = BPE_EHIP;
+    return;
+  }
+  g_num_cus = prop.multiProcessorCount;
+  for (auto& v : g_variants) {
+    if (v.lds > 48 * 1024) {
+      if (hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds) != hipSuccess) {
+        g_variants_status = BPE_EHIP;
+        return;
+      }
+    }
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, v.fn, v.waves * 64, v.lds) != hipSuccess ||
+        per_cu < 1) {
+      g_variants_status = BPE_EHIP;
+      return;
+    }
+    v.max_grid = per_cu * g_num_cus;
+  }
+}
+
+int n_tiers_for(int32_t max_len) {
+  int n = 1;
+  while (n < kMaxTiers && g_variants[n - 1].capacity < max_len) ++n;
+  return n;
+}
+
+// Staged variant: resident workgroups each own one staging slab; the grid is capped so that the slabs
+// stay modest (each is 512 KiB for 64 KiB strings).
+constexpr int kMaxStagedGrid = 256;
+size_t staged_slab_bytes(const Variant& v) { return (size_t)2 * 64 * v.waves * v.depth * sizeof(uint32_t); }
+
+constexpr size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WorkspaceLayout {
+  size_t control, list, counts, tmp_ids, staged, total;
+};
+
+WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) {
+  WorkspaceLayout w;
+  size_t at = 0;
+  w.control = at; at += align_up(sizeof(Control));
+  w.list = at; at += align_up((size_t)batch * sizeof(int32_t));
+  w.counts = at; at += align_up((size_t)batch * sizeof(int32_t));
+  w.tmp_ids = at; at += align_up((size_t)total_bytes * sizeof(int32_t));
+  w.staged = at;
+  const int nt = n_tiers_for(max_len);
+  for (int t = 0; t < nt; ++t)
+    if (g_variants[t].staged) at += align_up(staged_slab_bytes(g_variants[t]) * kMaxStagedGrid);
+  w.total = at;
+  return w;
+}
+
+thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
+thread_local bool t_ev_valid = false;
+bool g_profiling = false;
+
+}  // namespace
+
+extern "C" {
+
+int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, int32_t* bad_row) {
+  if (bad_row) *bad_row = -1;
+  if (!out) return BPE_EINVAL;
+  *out = nullptr;
+  if (n_merges < 0 || (n_merges > 0 && !merges)) return BPE_EINVAL;
+  if (n_merges > BPE_MAX_MERGES) return BPE_ETOOBIG;
+
+  // operands must exist before the row that uses them
+  for (int32_t r = 0; r < n_merges; ++r) {
+    const int32_t a = merges[2 * r], b = merges[2 * r + 1];
+    if (a < 0 || b < 0 || a >= 256 + r || b >= 256 + r) {
+      if (bad_row) *bad_row = r;
+      return BPE_EBADMERGE;
+    }
+  }
+
+  int log2_buckets = 6;
+  while ((int64_t)kSlotsPerBucket * ((int64_t)1 << log2_buckets) * 2 < (int64_t)n_merges * 5) ++log2_buckets;
+  const size_t n_buckets = (size_t)1 << log2_buckets;
+  const uint32_t bucket_mask = (uint32_t)n_buckets - 1;
+  const size_t n_words = n_buckets * kSlotsPerBucket * 2;      // uint32 words
+
+  std::vector<uint32_t> host;
+  std::vector<uint8_t> can_left, can_right;
+  try {
+    host.assign(n_words + 256, 0xFFFFFFFFu);
+    can_left.assign((size_t)n_merges + 256, 0);
+    can_right.assign((size_t)n_merges + 256, 0);
+  } catch (const std::bad_alloc&) {
+    return BPE_ENOMEM;
+  }
+  for (int32_t r = 0; r < n_merges; ++r) {
+    can_left[(size_t)merges[2 * r]] = 1;
+    can_right[(size_t)merges[2 * r + 1]] = 1;
+  }
+  for (int32_t r = 0; r < n_merges; ++r) {
+    const uint32_t a = (uint32_t)merges[2 * r], b = (uint32_t)merges[2 * r + 1];
+    uint32_t value = ((uint32_t)r << kFlagBits) | (a == b ? kFlagSelf : 0u) |
+                     (can_left[256 + (size_t)r] ? kFlagLeft : 0u) | (can_right[256 + (size_t)r] ? kFlagRight : 0u);
+    const uint32_t hi = slot_hi(a, b), lo = slot_lo(b, value);
+    uint32_t h = bucket_of(a, b, log2_buckets);
+    bool placed = false;
+    while (!placed) {
+      uint32_t* bucket = host.data() + (size_t)h * kSlotsPerBucket * 2;
+      for (int k = 0; k < kSlotsPerBucket; ++k) {
+        uint32_t& slo = bucket[2 * k];
+        uint32_t& shi = bucket[2 * k + 1];
+        if (shi == 0xFFFFFFFFu) {                      // first empty slot of the bucket
+          slo = lo;
+          shi = hi;
+          placed = true;
+          break;
+        }
+        if (shi == hi && (slo >> 24) == (b & 0xFFu)) { // the pair is already there
+          if (bad_row) *bad_row = r;
+          return BPE_EDUPPAIR;
+        }
+      }
+      if (!placed) h = (h + 1) & bucket_mask;
+    }
+  }
+  uint32_t* byte_word = host.data() + n_words;
+  for (uint32_t b = 0; b < 256; ++b)
+    byte_word[b] = b | (can_left[b] ? kTokCanLeft : 0u) | (can_right[b] ? kTokCanRight : 0u);
+
+  bpe_table* t = new (std::nothrow) bpe_table();
+  if (!t) return BPE_ENOMEM;
+  t->n_merges = n_merges;
+  t->log2_buckets = log2_buckets;
+  t->bucket_bytes = n_words * sizeof(uint32_t);
+  if (hipGetDevice(&t->device) != hipSuccess) { delete t; return BPE_EHIP; }
+  hipError_t e = hipMalloc(&t->d_mem, host.size() * sizeof(uint32_t));
+  if (e != hipSuccess) { delete t; return e == hipErrorOutOfMemory ? BPE_ENOMEM : BPE_EHIP; }
+  if (hipMemcpy(t->d_mem, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(t->d_mem);
+    delete t;
+    return BPE_EHIP;
+  }
+  *out = t;
+  return BPE_OK;
+}
+
+void bpe_free_table(bpe_table* table) {
+  if (!table) return;
+  if (table->d_mem) (void)hipFree(table->d_mem);
+  delete table;
+}
+
+int32_t bpe_table_n_merges(const bpe_table* table) { return table ? table->n_merges : 0; }
+
+size_t bpe_workspace_bytes(int32_t batch, int64_t total_bytes, int32_t max_len) {
+  if (batch < 0 || total_bytes < 0 || max_len < 0 || max_len > BPE_MAX_STRING_BYTES) return 0;
+  return layout_for(batch, total_bytes, max_len).total;
+}
+
+int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                     int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
+                     void* workspace, size_t workspace_bytes, void* stream_ptr) {
+  if (!table || batch < 0 || total_bytes < 0 || max_len < 0 || max_len > BPE_MAX_STRING_BYTES)
+    return BPE_EINVAL;
+  if (!offsets || !out_offsets || !workspace) return BPE_EINVAL;
+  if (total_bytes > 0 && (!bytes || !out_ids)) return BPE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0) return BPE_EINVAL;
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return BPE_EHIP;
+  if (device != table->device) return BPE_EINVAL;
+  const WorkspaceLayout w = layout_for(batch, total_bytes, max_len);
+  if (workspace_bytes < w.total) return BPE_EINVAL;
+
+  std::call_once(g_variants_once, init_variants);
+  if (g_variants_status != BPE_OK) return g_variants_status;
+
+  hipStream_t stream = (hipStream_t)stream_ptr;
+  char* ws = (char*)workspace;
+  Control* ctrl = (Control*)(ws + w.control);
+  int32_t* list = (int32_t*)(ws + w.list);
+  int32_t* counts = (int32_t*)(ws + w.counts);
+  int32_t* tmp_ids = (int32_t*)(ws + w.tmp_ids);
+
+  TierPlan plan;
+  plan.n_tiers = n_tiers_for(max_len);
+  for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_variants[t].capacity;
+
+  hipLaunchKernelGGL(zero_control_kernel, dim3(1), dim3(256), 0, stream, ctrl);
+  if (batch > 0) {
+    const int blocks = (batch + 255) / 256;
+    hipLaunchKernelGGL(bin_count_kernel, dim3(blocks), dim3(256), 0, stream, offsets, batch, plan, ctrl, counts);
+    hipLaunchKernelGGL(bin_scan_kernel, dim3(1), dim3(kBinKeys), 0, stream, ctrl, plan.n_tiers);
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(blocks), dim3(256), 0, stream, offsets, batch, plan, ctrl, list);
+
+    EncodeParams p;
+    p.table.buckets = (const uint4*)table->d_mem;
+    p.table.byte_word = (const uint32_t*)((const char*)table->d_mem + table->bucket_bytes);
+    p.table.log2_buckets = table->log2_buckets;
+    p.table.bucket_mask = ((uint32_t)1 << table->log2_buckets) - 1;
+    p.bytes = bytes;
+    p.offsets = offsets;
+    p.list = list;
+    p.tier_base = ctrl->tier_base;
+    p.queue_head = ctrl->queue_head;
+    p.tmp_ids = tmp_ids;
+    p.counts = counts;
+
+    const bool prof = g_profiling;
+    if (prof) {
+      if (!t_ev_begin && (hipEventCreate(&t_ev_begin) != hipSuccess || hipEventCreate(&t_ev_end) != hipSuccess))
+        return BPE_EHIP;
+      if (hipEventRecord(t_ev_begin, stream) != hipSuccess) return BPE_EHIP;
+    }
+    size_t staged_at = w.staged;
+    for (int t = 0; t < plan.n_tiers; ++t) {
+      const Variant& v = g_variants[t];
+      int grid = v.max_grid < batch ? v.max_grid : batch;
+      p.tier = t;
+      p.staged = nullptr;
+      if (v.staged) {
+        if (grid > kMaxStagedGrid) grid = kMaxStagedGrid;
+        p.staged = (uint32_t*)(ws + staged_at);
+        staged_at += align_up(staged_slab_bytes(v) * kMaxStagedGrid);
+      }
+      v.launch(p, grid, stream);
+    }
+    if (prof) {
+      if (hipEventRecord(t_ev_end, stream) != hipSuccess) return BPE_EHIP;
+      t_ev_valid = true;
+    }
+  }
+  hipLaunchKernelGGL(offsets_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, batch, out_offsets);
+  if (batch > 0) {
+    const int grid = batch < 65536 ? batch : 65536;
+    hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, offsets, out_offsets, batch, out_ids);
+  }
+  return hipGetLastError() == hipSuccess ? BPE_OK : BPE_EHIP;
+}
+
+void bpe_set_profiling(int enabled) { g_profiling = enabled != 0; }
+
+float bpe_last_encode_kernel_ms(void) {
+  if (!t_ev_valid) return -1.0f;
+  float ms = -1.0f;
+  if (hipEventSynchronize(t_ev_end) != hipSuccess) return -1.0f;
+  if (hipEventElapsedTime(&ms, t_ev_begin, t_ev_end) != hipSuccess) return -1.0f;
+  return ms;
+}
+
+const char* bpe_strerror(int code) {
+  switch (code) {
+    case BPE_OK: return "ok";
+    case BPE_EINVAL: return "invalid argument";
+    case BPE_EBADMERGE: return "merge row uses a token id that does not exist before that row";
+    case BPE_EDUPPAIR: return "the same pair appears in two merge rows";
+    case BPE_ENOMEM: return "out of memory";
+    case BPE_EHIP: return "HIP runtime call failed";
+    case BPE_ETOOBIG: return "too many merge rows for the table format";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"
