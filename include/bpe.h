@@ -72,11 +72,10 @@ size_t bpe_workspace_bytes(int32_t batch, int64_t total_bytes, int32_t max_len);
  *                non-decreasing, offsets[batch] = total_bytes.  Any byte sequence is valid input.
  *   batch        number of strings, >= 0.
  *   total_bytes  offsets[batch], passed by the host so that the call needs no device-to-host read.
- *   max_len      an upper bound on the longest string, <= BPE_MAX_STRING_BYTES.  It selects which kernel
- *                variants are launched.  A string longer than max_len makes the call's output undefined for
- *                that string only if it also exceeds BPE_MAX_STRING_BYTES; otherwise it is still encoded
- *                correctly as long as max_len was large enough to launch its variant -- pass the true
- *                maximum.
+ *   max_len      an upper bound on the longest string, <= BPE_MAX_STRING_BYTES, passed by the host for the
+ *                same reason.  It selects which kernel variants are launched.  Pass the true maximum: a
+ *                string too long for the variants that max_len selects is not encoded and contributes zero
+ *                tokens (no out-of-bounds access happens).
  *   out_ids      DEVICE, int32, capacity >= total_bytes ids (a string never has more tokens than bytes).
  *   out_offsets  DEVICE, int64[batch+1].
  *   workspace    DEVICE, >= bpe_workspace_bytes(batch, total_bytes, max_len) bytes, 256-byte aligned,
@@ -92,14 +91,15 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
                      int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
                      void* workspace, size_t workspace_bytes, void* stream);
 
-/* Duration in milliseconds of the encode kernels of the most recent bpe_encode_batch on this thread whose
- * profiling was requested with bpe_set_profiling(1): HIP events recorded on the call's own stream around the
- * per-string encode kernels only (not the binning, offset scan or packing kernels).  Synchronises on those
- * events.  Returns a negative value if no such measurement exists. */
-float bpe_last_encode_kernel_ms(void);
-
-/* Turn the event recording above on (non-zero) or off (0, the default).  Per process. */
+/* Timing of the per-string encode kernels alone (not the binning, offset-scan or packing kernels), for
+ * roofline accounting.  bpe_set_profiling(1) switches it on and clears the record; from then on every
+ * bpe_encode_batch (up to 512 calls) records a pair of HIP events on its own stream around its encode
+ * kernels.  bpe_set_profiling(0) switches it off (the default).  Process-wide. */
 void bpe_set_profiling(int enabled);
+
+/* Sum of the recorded encode-kernel durations in milliseconds and the number of calls recorded since
+ * profiling was switched on.  total_ms, calls: HOST.  Waits for the recorded events to complete. */
+int bpe_read_profile(float* total_ms, int32_t* calls);
 
 /* Human-readable text for a BPE_* code. */
 const char* bpe_strerror(int code);

@@ -42,8 +42,8 @@ def load_library():
     lib.bpe_workspace_bytes.restype = ctypes.c_size_t
     lib.bpe_encode_batch.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.bpe_encode_batch.restype = ctypes.c_int
-    lib.bpe_last_encode_kernel_ms.argtypes = []
-    lib.bpe_last_encode_kernel_ms.restype = ctypes.c_float
+    lib.bpe_read_profile.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    lib.bpe_read_profile.restype = ctypes.c_int
     lib.bpe_set_profiling.argtypes = [ctypes.c_int]
     lib.bpe_set_profiling.restype = None
     lib.bpe_strerror.argtypes = [ctypes.c_int]
@@ -135,5 +135,8 @@ def set_profiling(enabled: bool) -> None:
     load_library().bpe_set_profiling(1 if enabled else 0)
 
 
-def last_encode_kernel_ms() -> float:
-    return float(load_library().bpe_last_encode_kernel_ms())
+def read_profile():
+    """(total encode-kernel milliseconds, number of calls) recorded since set_profiling(True)."""
+    total, calls = ctypes.c_float(0.0), ctypes.c_int32(0)
+    _check(load_library().bpe_read_profile(ctypes.byref(total), ctypes.byref(calls)), "bpe_read_profile")
+    return float(total.value), int(calls.value)

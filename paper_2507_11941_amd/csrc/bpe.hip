@@ -127,8 +127,15 @@ WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) 
   return w;
 }
 
-thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
-thread_local bool t_ev_valid = false;
+// Optional timing of the encode kernels alone: a ring of event pairs recorded on the caller's stream.
+constexpr int kProfileRing = 512;
+struct ProfileRing {
+  hipEvent_t begin[kProfileRing], end[kProfileRing];
+  int created = 0;   // event pairs that exist
+  int used = 0;      // pairs recorded since profiling was switched on
+};
+ProfileRing g_prof;
+std::mutex g_prof_mutex;
 bool g_profiling = false;
 
 }  // namespace
@@ -278,11 +285,19 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     p.tmp_ids = tmp_ids;
     p.counts = counts;
 
-    const bool prof = g_profiling;
-    if (prof) {
-      if (!t_ev_begin && (hipEventCreate(&t_ev_begin) != hipSuccess || hipEventCreate(&t_ev_end) != hipSuccess))
-        return BPE_EHIP;
-      if (hipEventRecord(t_ev_begin, stream) != hipSuccess) return BPE_EHIP;
+    int prof_slot = -1;
+    if (g_profiling) {
+      std::lock_guard<std::mutex> lock(g_prof_mutex);
+      if (g_prof.used < kProfileRing) {
+        if (g_prof.used == g_prof.created) {
+          if (hipEventCreate(&g_prof.begin[g_prof.created]) != hipSuccess ||
+              hipEventCreate(&g_prof.end[g_prof.created]) != hipSuccess)
+            return BPE_EHIP;
+          ++g_prof.created;
+        }
+        prof_slot = g_prof.used++;
+        if (hipEventRecord(g_prof.begin[prof_slot], stream) != hipSuccess) return BPE_EHIP;
+      }
     }
     size_t staged_at = w.staged;
     for (int t = 0; t < plan.n_tiers; ++t) {
@@ -297,10 +312,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
       }
       v.launch(p, grid, stream);
     }
-    if (prof) {
-      if (hipEventRecord(t_ev_end, stream) != hipSuccess) return BPE_EHIP;
-      t_ev_valid = true;
-    }
+    if (prof_slot >= 0 && hipEventRecord(g_prof.end[prof_slot], stream) != hipSuccess) return BPE_EHIP;
   }
   hipLaunchKernelGGL(offsets_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, batch, out_offsets);
   if (batch > 0) {
@@ -310,14 +322,26 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   return hipGetLastError() == hipSuccess ? BPE_OK : BPE_EHIP;
 }
 
-void bpe_set_profiling(int enabled) { g_profiling = enabled != 0; }
+void bpe_set_profiling(int enabled) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  g_profiling = enabled != 0;
+  g_prof.used = 0;
+}
 
-float bpe_last_encode_kernel_ms(void) {
-  if (!t_ev_valid) return -1.0f;
-  float ms = -1.0f;
-  if (hipEventSynchronize(t_ev_end) != hipSuccess) return -1.0f;
-  if (hipEventElapsedTime(&ms, t_ev_begin, t_ev_end) != hipSuccess) return -1.0f;
-  return ms;
+int bpe_read_profile(float* total_ms, int32_t* calls) {
+  if (!total_ms || !calls) return BPE_EINVAL;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  float sum = 0.0f;
+  for (int i = 0; i < g_prof.used; ++i) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(g_prof.end[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_prof.begin[i], g_prof.end[i]) != hipSuccess)
+      return BPE_EHIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *calls = g_prof.used;
+  return BPE_OK;
 }
 
 const char* bpe_strerror(int code) {
