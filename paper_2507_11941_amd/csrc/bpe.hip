@@ -158,54 +158,73 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
     }
   }
 
-  int log2_buckets = 6;
-  while ((int64_t)kSlotsPerBucket * ((int64_t)1 << log2_buckets) * 2 < (int64_t)n_merges * 5) ++log2_buckets;
-  const size_t n_buckets = (size_t)1 << log2_buckets;
-  const uint32_t bucket_mask = (uint32_t)n_buckets - 1;
-  const size_t n_words = n_buckets * kSlotsPerBucket * 2;      // uint32 words
-
   std::vector<uint32_t> host;
-  std::vector<uint8_t> can_left, can_right;
+  std::vector<int32_t> first_left, first_right;                // first row that uses a token as left / right
   try {
-    host.assign(n_words + 256, 0xFFFFFFFFu);
-    can_left.assign((size_t)n_merges + 256, 0);
-    can_right.assign((size_t)n_merges + 256, 0);
+    first_left.assign((size_t)n_merges + 256, -1);
+    first_right.assign((size_t)n_merges + 256, -1);
   } catch (const std::bad_alloc&) {
     return BPE_ENOMEM;
   }
   for (int32_t r = 0; r < n_merges; ++r) {
-    can_left[(size_t)merges[2 * r]] = 1;
-    can_right[(size_t)merges[2 * r + 1]] = 1;
+    int32_t& fl = first_left[(size_t)merges[2 * r]];
+    int32_t& fr = first_right[(size_t)merges[2 * r + 1]];
+    if (fl < 0) fl = r;
+    if (fr < 0) fr = r;
   }
-  for (int32_t r = 0; r < n_merges; ++r) {
-    const uint32_t a = (uint32_t)merges[2 * r], b = (uint32_t)merges[2 * r + 1];
-    uint32_t value = ((uint32_t)r << kFlagBits) | (a == b ? kFlagSelf : 0u) |
-                     (can_left[256 + (size_t)r] ? kFlagLeft : 0u) | (can_right[256 + (size_t)r] ? kFlagRight : 0u);
-    const uint32_t hi = slot_hi(a, b), lo = slot_lo(b, value);
-    uint32_t h = bucket_of(a, b, log2_buckets);
-    bool placed = false;
-    while (!placed) {
-      uint32_t* bucket = host.data() + (size_t)h * kSlotsPerBucket * 2;
-      for (int k = 0; k < kSlotsPerBucket; ++k) {
-        uint32_t& slo = bucket[2 * k];
-        uint32_t& shi = bucket[2 * k + 1];
-        if (shi == 0xFFFFFFFFu) {                      // first empty slot of the bucket
-          slo = lo;
-          shi = hi;
-          placed = true;
-          break;
-        }
-        if (shi == hi && (slo >> 24) == (b & 0xFFu)) { // the pair is already there
-          if (bad_row) *bad_row = r;
-          return BPE_EDUPPAIR;
+
+  int log2_buckets = kMinLog2Buckets;
+  while ((int64_t)kSlotsPerBucket * ((int64_t)1 << log2_buckets) * 2 < (int64_t)n_merges * 5) ++log2_buckets;
+  size_t n_words = 0;
+  for (;; ++log2_buckets) {                                    // grow until every key sits close to home
+    if (log2_buckets > kMaxLog2Buckets) return BPE_ETOOBIG;
+    const size_t n_buckets = (size_t)1 << log2_buckets;
+    const uint32_t bucket_mask = (uint32_t)n_buckets - 1;
+    n_words = n_buckets * kSlotsPerBucket * 2;                 // uint32 words
+    try {
+      host.assign(n_words + 256, 0xFFFFFFFFu);
+    } catch (const std::bad_alloc&) {
+      return BPE_ENOMEM;
+    }
+    bool fits = true;
+    for (int32_t r = 0; r < n_merges && fits; ++r) {
+      const uint32_t a = (uint32_t)merges[2 * r], b = (uint32_t)merges[2 * r + 1];
+      const int32_t fl = first_left[256 + (size_t)r], fr = first_right[256 + (size_t)r];
+      // horizon: ranks between this row and the first later row that uses its token (rows only use
+      // older tokens, so that row comes after this one)
+      uint32_t code = 255;
+      if (fl >= 0 || fr >= 0) {
+        const int32_t first_use = fl < 0 ? fr : (fr < 0 ? fl : (fl < fr ? fl : fr));
+        code = horizon_encode((uint32_t)(first_use - r - 1));
+      }
+      const uint32_t value = make_value((uint32_t)r, code, fl >= 0, fr >= 0);
+      const Placement pl = place_pair(a, b, log2_buckets);
+      bool placed = false;
+      for (uint32_t step = 0; step <= kMaxDisplacement && !placed; ++step) {
+        uint32_t* bucket = host.data() + (size_t)((pl.bucket + step) & bucket_mask) * kSlotsPerBucket * 2;
+        const uint32_t tag = slot_tag(pl.fingerprint, step);
+        for (int k = 0; k < kSlotsPerBucket; ++k) {
+          uint32_t& slo = bucket[2 * k];
+          uint32_t& shi = bucket[2 * k + 1];
+          if (shi == 0xFFFFFFFFu) {                            // first empty slot of the bucket
+            slo = value;
+            shi = tag;
+            placed = true;
+            break;
+          }
+          if (shi == tag) {                                    // same home bucket, same fingerprint: same pair
+            if (bad_row) *bad_row = r;
+            return BPE_EDUPPAIR;
+          }
         }
       }
-      if (!placed) h = (h + 1) & bucket_mask;
+      fits = placed;
     }
+    if (fits) break;
   }
   uint32_t* byte_word = host.data() + n_words;
   for (uint32_t b = 0; b < 256; ++b)
-    byte_word[b] = b | (can_left[b] ? kTokCanLeft : 0u) | (can_right[b] ? kTokCanRight : 0u);
+    byte_word[b] = b | (first_left[b] >= 0 ? kTokCanLeft : 0u) | (first_right[b] >= 0 ? kTokCanRight : 0u);
 
   bpe_table* t = new (std::nothrow) bpe_table();
   if (!t) return BPE_ENOMEM;

@@ -1,32 +1,38 @@
 // Per-string BPE merge kernel for gfx950 (wave64).
 //
 // One workgroup encodes one string (section 4.3: one block per string) and repeats merge passes until no
-// adjacent pair is in the table (section 4.2): (1-2) every adjacent pair's rank is known, (3) workgroup
-// minimum, (4) mark the occurrences of that rank, left-most first where they overlap, (5) write the merged
-// token.  All occurrences of the pass's rank are applied in the same pass; because every row's operands
-// are older than the row, this equals Algorithm 1's one-at-a-time order.
+// adjacent pair is in the table (section 4.2): every adjacent pair's rank is known, a workgroup minimum
+// decides what may merge, the occurrences are marked -- left-most first where they overlap -- and the
+// merged tokens are written.
 //
-// How the passes are organised here (differs from the paper's compaction-per-pass):
-//   * Lane `tid` owns the d = ceil(n / W) consecutive byte positions [tid*d, tid*d + d) of its string for
-//     the whole encode.  A position holds a token word and the cached rank value of the pair (this token,
-//     next live token).  Position e of lane tid lives at index e*W + tid, so a wave touches 64 consecutive
-//     words whatever e each lane is at: no LDS bank conflicts, coalesced when the arrays are in HBM.
-//   * A merge keeps the merged token at the left position and kills the right one; liveness is a bit mask
-//     in a register.  Nothing moves, so a pass costs the reduction plus work only in lanes that hold the
-//     minimum; the paper's prefix-sum compaction (section 4.3) runs once, at the end, to emit the ids.
+// What differs from the paper's kernel, and why it is still Algorithm 1's result:
+//
+//   * Many ranks per pass.  The paper applies the single lowest rank per pass.  Here a pass takes the
+//     workgroup minimum E of limit() over all present pairs (see table_format.h): no pair that can still
+//     appear has a rank below E, so the present pairs with rank < E ("candidates") can be settled among
+//     themselves.  Algorithm 1 would take them in (rank, position) order, and a candidate is lost only
+//     if an adjacent candidate with better priority is applied first.  Candidates form runs; inside a
+//     run, going right while ranks do not decrease, the applied ones alternate starting with the run's
+//     head (for a self pair such as (a,a) in "aaaa" this is the left-most-first rule).  A candidate whose
+//     right neighbour has a strictly lower rank is left for the next pass: by then the neighbour has
+//     either consumed it or been consumed itself.  Applying a subset of the merges Algorithm 1 is bound
+//     to apply never changes the result, because merges of non-adjacent pairs commute.
+//     Passes drop by 4-12x on the benchmark workloads; each pass is one reduction, not one per rank.
+//   * No compaction per pass across the workgroup.  Lane `tid` owns the d = ceil(n / W) consecutive byte
+//     positions [tid*d, tid*d + d) of its string for the whole encode and keeps its live tokens compacted
+//     inside its own column (slot k of lane tid is word k*W + tid: conflict-free in LDS, coalesced in
+//     HBM).  A merged token stays with the lane of its left operand.  The paper's prefix-sum compaction
+//     (section 4.3) runs once, at the end, to emit the ids.
 //   * Ranks are looked up when a pair is created (n-1 initial probes, at most two per merge), never
-//     re-probed per pass; a lane keeps the minimum of its cached ranks in a register.
-//   * The only data that crosses lanes: each lane's first live token, so that the previous non-empty lane
-//     can form its boundary pair; a "your first token was consumed" bit; and the reductions.  Inside a
-//     wave these travel through ballots and lane permutes (registers only), between waves through a few
-//     words of LDS per wave.  A one-wave workgroup therefore needs no barrier at all.
-//   * Self pairs (left == right, e.g. runs "aaaa"): occurrences overlap, so the pass numbers the live
-//     tokens (prefix sum), finds each run's start (prefix max) and keeps every second occurrence counted
-//     from the run start.
+//     re-probed per pass.
+//   * Lanes exchange only boundary data: the value of the previous lane's last pair and of the next
+//     lane's first pair, the next lane's first token, and a 2-bit segmented-scan element that carries
+//     the parity of a run across lanes.  Inside a wave these travel through ballots and lane permutes
+//     (registers only); between waves through one small LDS record per wave.  A one-wave workgroup
+//     therefore needs no barrier at all.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <type_traits>
 
 #include "table_format.h"
 
@@ -55,124 +61,117 @@ struct EncodeParams {
 // ---------------------------------------------------------------------------------------------------
 // wave64 primitives
 
-__device__ inline uint32_t dpp_quad_xor1(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false);  // quad_perm 1,0,3,2
-}
-__device__ inline uint32_t dpp_quad_xor2(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false);  // quad_perm 2,3,0,1
-}
-__device__ inline uint32_t dpp_half_mirror(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false);
-}
-__device__ inline uint32_t dpp_row_mirror(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xF, 0xF, false);
-}
+__device__ inline uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
-// Minimum over the 64 lanes, returned in every lane.  All lanes must be active.
-__device__ inline uint32_t wave_min(uint32_t v) {
-  v = min(v, dpp_quad_xor1(v));
-  v = min(v, dpp_quad_xor2(v));
-  v = min(v, dpp_half_mirror(v));
-  v = min(v, dpp_row_mirror(v));   // every lane of a 16-lane row now holds the row minimum
-  uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
-  uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
-  uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
-  uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
-  return min(min(a, b), min(c, d));
+template <int CTRL>
+__device__ inline uint32_t dpp(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
 }
+constexpr int kDppQuadXor1 = 0xB1;      // quad_perm 1,0,3,2
+constexpr int kDppQuadXor2 = 0x4E;      // quad_perm 2,3,0,1
+constexpr int kDppHalfMirror = 0x141;   // row_half_mirror
+constexpr int kDppRowMirror = 0x140;    // row_mirror
 
-struct OpAdd { __device__ static uint32_t apply(uint32_t a, uint32_t b) { return a + b; } };
+struct OpMin { __device__ static uint32_t apply(uint32_t a, uint32_t b) { return a < b ? a : b; } };
 struct OpMax { __device__ static uint32_t apply(uint32_t a, uint32_t b) { return a > b ? a : b; } };
 
-// Inclusive scan over the wave (identity 0 for both operators).
+// Reduction over the 64 lanes, uniform (scalar) result.  All lanes must be active.
 template <class Op>
-__device__ inline uint32_t wave_scan_inclusive(uint32_t v, int lane) {
+__device__ inline uint32_t wave_reduce(uint32_t v) {
+  v = Op::apply(v, dpp<kDppQuadXor1>(v));
+  v = Op::apply(v, dpp<kDppQuadXor2>(v));
+  v = Op::apply(v, dpp<kDppHalfMirror>(v));
+  v = Op::apply(v, dpp<kDppRowMirror>(v));   // every lane of a 16-lane row now holds the row's result
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return Op::apply(Op::apply(a, b), Op::apply(c, d));
+}
+
+__device__ inline uint32_t lane_read(uint32_t v, int src_lane) { return (uint32_t)__shfl((int)v, src_lane, 64); }
+
+// Inclusive prefix sum over the wave.
+__device__ inline uint32_t wave_prefix_sum(uint32_t v, int lane) {
 #pragma unroll
   for (int step = 1; step < 64; step <<= 1) {
-    uint32_t o = (uint32_t)__shfl_up((int)v, step, 64);
-    if (lane >= step) v = Op::apply(v, o);
+    const uint32_t o = (uint32_t)__shfl_up((int)v, step, 64);
+    if (lane >= step) v += o;
   }
   return v;
 }
 
-template <class T> __device__ inline int ctz_bits(T m);
-template <> __device__ inline int ctz_bits<uint32_t>(uint32_t m) { return __builtin_ctz(m); }
-template <> __device__ inline int ctz_bits<uint64_t>(uint64_t m) { return __builtin_ctzll(m); }
-template <class T> __device__ inline int top_bit(T m);
-template <> __device__ inline int top_bit<uint32_t>(uint32_t m) { return 31 - __builtin_clz(m); }
-template <> __device__ inline int top_bit<uint64_t>(uint64_t m) { return 63 - __builtin_clzll(m); }
-template <class T> __device__ inline int pop_bits(T m);
-template <> __device__ inline int pop_bits<uint32_t>(uint32_t m) { return __builtin_popcount(m); }
-template <> __device__ inline int pop_bits<uint64_t>(uint64_t m) { return __builtin_popcountll(m); }
+// Run-parity element: bit 1 = "a run restarts inside", bit 0 = parity of the run length since the last
+// restart (or of the whole span if none).  combine(left, right) is the element of the concatenation.
+__device__ inline uint32_t parity_combine(uint32_t left, uint32_t right) {
+  return (right & 2u) ? right : ((left & 2u) | ((left ^ right) & 1u));
+}
+__device__ inline uint32_t wave_parity_scan(uint32_t v, int lane) {   // inclusive
+#pragma unroll
+  for (int step = 1; step < 64; step <<= 1) {
+    const uint32_t o = (uint32_t)__shfl_up((int)v, step, 64);
+    if (lane >= step) v = parity_combine(o, v);
+  }
+  return v;
+}
 
 // ---------------------------------------------------------------------------------------------------
 // table probe
 
 __device__ inline uint32_t probe_ids(const DeviceTable& t, uint32_t a, uint32_t b) {
-  uint32_t h = bucket_of(a, b, t.log2_buckets);
-  const uint32_t hi = slot_hi(a, b), lo8 = b & 0xFFu;
-  for (;;) {
-    const uint4* p = t.buckets + 2 * (size_t)h;
+  const Placement pl = place_pair(a, b, t.log2_buckets);
+  for (uint32_t step = 0; step <= kMaxDisplacement; ++step) {
+    const uint4* p = t.buckets + 2 * (size_t)((pl.bucket + step) & t.bucket_mask);
     const uint4 x = p[0], y = p[1];
-    if (x.y == hi && (x.x >> 24) == lo8) return x.x & 0xFFFFFFu;
-    if (x.w == hi && (x.z >> 24) == lo8) return x.z & 0xFFFFFFu;
-    if (y.y == hi && (y.x >> 24) == lo8) return y.x & 0xFFFFFFu;
-    if (y.w == hi && (y.z >> 24) == lo8) return y.z & 0xFFFFFFu;
-    if (y.w == 0xFFFFFFFFu) return kNoRank;   // bucket not full: the key is nowhere else
-    h = (h + 1) & t.bucket_mask;
+    const uint32_t tag = slot_tag(pl.fingerprint, step);
+    if (x.y == tag) return x.x;
+    if (x.w == tag) return x.z;
+    if (y.y == tag) return y.x;
+    if (y.w == tag) return y.z;
+    if (y.w == 0xFFFFFFFFu) break;            // bucket not full: the key is nowhere else
   }
+  return kNoRank;
 }
 
-// Rank value of the pair of two token words, skipping the probe when the capability bits rule it out.
+// Value of the pair of two token words, skipping the probe when the capability bits rule it out.
 __device__ inline uint32_t probe_words(const DeviceTable& t, uint32_t x, uint32_t y) {
   if (!(x & kTokCanLeft) || !(y & kTokCanRight)) return kNoRank;
   return probe_ids(t, x & kTokIdMask, y & kTokIdMask);
 }
 
 // ---------------------------------------------------------------------------------------------------
+// workgroup-level exchange (only used when the workgroup has more than one wave)
+
+// What a wave tells the others after each pass.
+struct WaveRecord {
+  uint32_t limit;      // min limit() over the wave's pairs, kNoRank if it has none
+  uint32_t first_val;  // pair value at the wave's first live token (kNoRank if none / wave empty)
+  uint32_t last_val;   // pair value at the wave's last live token
+  uint32_t first_tok;  // first live token word, kTokNone if the wave is empty
+};
 
 template <int NW>
 struct BlockShared {
-  uint32_t* wave_tok;    // [2*NW] first live token word of each wave (kTokNone if empty), double buffered
-  uint32_t* wave_cross;  // [NW] 1 if the wave's last non-empty lane merged across the wave boundary
-  uint32_t* red;         // [2*NW] minimum partials, double buffered
+  WaveRecord* rec;       // [2][NW] double buffered by pass parity
+  uint32_t* first_tok;   // [2][NW] first live token of each wave after the pass's merges
   uint32_t* part;        // [NW] scan partials
   uint32_t* item;        // [1] work item broadcast
 };
 
-__device__ inline uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
-
-// Workgroup barrier; a single-wave workgroup exchanges data through registers only and needs none.
 template <int NW>
 __device__ inline void block_sync() {
   if (NW > 1) __syncthreads();
 }
 
-// Minimum over the workgroup, uniform (scalar) result.
+// Exclusive prefix sum of v over the workgroup in lane order; *total receives the sum.
 template <int NW>
-__device__ inline uint32_t block_min(uint32_t v, const BlockShared<NW>& sh, int wave, int parity) {
-  v = wave_min(v);
-  if (NW == 1) return v;
-  uint32_t* red = sh.red + parity * NW;
-  if ((threadIdx.x & 63) == 0) red[wave] = v;
-  __syncthreads();
-  uint32_t r = red[0];
-#pragma unroll
-  for (int w = 1; w < NW; ++w) r = min(r, red[w]);
-  return uniform(r);
-}
-
-// Exclusive scan of v over the workgroup in lane order; *total receives the full reduction.
-template <int NW, class Op>
-__device__ inline uint32_t block_scan_exclusive(uint32_t v, const BlockShared<NW>& sh, int lane, int wave,
-                                                uint32_t* total) {
-  uint32_t inc = wave_scan_inclusive<Op>(v, lane);
-  uint32_t exc = (uint32_t)__shfl_up((int)inc, 1, 64);
-  if (lane == 0) exc = 0;
-  uint32_t wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+__device__ inline uint32_t block_prefix_sum(uint32_t v, const BlockShared<NW>& sh, int lane, int wave,
+                                            uint32_t* total) {
+  const uint32_t inc = wave_prefix_sum(v, lane);
+  const uint32_t wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
   if (NW == 1) {
     *total = wave_total;
-    return exc;
+    return inc - v;
   }
   __syncthreads();                       // previous users of sh.part are done
   if (lane == 0) sh.part[wave] = wave_total;
@@ -180,23 +179,43 @@ __device__ inline uint32_t block_scan_exclusive(uint32_t v, const BlockShared<NW
   uint32_t before = 0, all = 0;
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
-    uint32_t p = sh.part[w];
-    if (w < wave) before = Op::apply(before, p);
-    all = Op::apply(all, p);
+    const uint32_t p = sh.part[w];
+    if (w < wave) before += p;
+    all += p;
   }
   *total = all;
-  return Op::apply(before, exc);
+  return before + inc - v;
 }
 
-// Encode string s.  tok/rnk: token words and cached pair ranks, index e*W + tid, in LDS or (strings that
-// exceed LDS) in HBM; every word is read and written by its owning lane only.  Lanes of one wave exchange
-// data through ballots and lane permutes; waves exchange through the small LDS arrays of BlockShared.
+// My wave's record for the coming pass (no-op for a one-wave workgroup).
+template <int NW>
+__device__ inline void publish_record(const BlockShared<NW>& sh, int buf, int wave, int lane, int c,
+                                      uint32_t llim, uint32_t firstv, uint32_t lastv, uint32_t ftok) {
+  if (NW == 1) return;
+  const uint64_t ne = __ballot(c != 0);
+  const uint32_t wlim = wave_reduce<OpMin>(llim);
+  const int fl = ne ? __builtin_ctzll(ne) : 0, ll = ne ? 63 - __builtin_clzll(ne) : 0;
+  const uint32_t fv = lane_read(firstv, fl), ft = lane_read(ftok, fl), lv = lane_read(lastv, ll);
+  if (lane == 0) {
+    WaveRecord r;
+    r.limit = wlim;
+    r.first_val = ne ? fv : kNoRank;
+    r.last_val = ne ? lv : kNoRank;
+    r.first_tok = ne ? ft : kTokNone;
+    sh.rec[buf * NW + wave] = r;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Encode string s.  T/V: token words and pair values of each lane's live tokens, slot k of lane tid at
+// index k*W + tid, in LDS or (strings that exceed LDS) in HBM; every word is read and written by its
+// owning lane only.  V[k] is the value of the pair (token k, next live token of the string) -- for a
+// lane's last slot the next token is the first token of the next non-empty lane.
+
 template <int NW, int D, bool STAGED>
-__device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict__ tok,
-                              uint32_t* __restrict__ rnk, const BlockShared<NW>& sh) {
+__device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict__ T, uint32_t* __restrict__ V,
+                              const BlockShared<NW>& sh) {
   constexpr int W = NW * 64;
-  using mask_t = typename std::conditional<(D <= 32), uint32_t, uint64_t>::type;
-  constexpr int kBits = (int)sizeof(mask_t) * 8;
   const int tid = (int)threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -209,152 +228,203 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     return;
   }
   const uint8_t* src = p.bytes + begin;
-  const int d = (n + W - 1) / W;                       // positions per lane, 1 <= d <= D
-  int my_n = n - tid * d;
-  my_n = my_n < 0 ? 0 : (my_n > d ? d : my_n);
-
-  mask_t mask = my_n >= kBits ? ~(mask_t)0 : (((mask_t)1 << my_n) - 1);
+  const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D
+  int c = n - tid * d;                                 // my live token count
+  c = c < 0 ? 0 : (c > d ? d : c);
 
   // ---- load: byte-level pre-tokenisation (section 4.1), id = byte value ----
-  for (int e = 0; e < my_n; ++e) tok[e * W + tid] = tab.byte_word[src[tid * d + e]];
-  uint32_t ftok = my_n > 0 ? tok[tid] : kTokNone;      // my first live token word
+  for (int k = 0; k < c; ++k) T[k * W + tid] = tab.byte_word[src[tid * d + k]];
+  uint32_t ftok = c > 0 ? T[tid] : kTokNone;           // my first live token word
   // token my last pair is probed against: first token of the lane that follows (lanes fill contiguously)
   uint32_t succ_tok = kTokNone;
-  if (my_n > 0 && (tid + 1) * d < n) succ_tok = tab.byte_word[src[(tid + 1) * d]];
+  if (c > 0 && (tid + 1) * d < n) succ_tok = tab.byte_word[src[(tid + 1) * d]];
 
-  // ---- initial ranks: one probe per adjacent pair ----
-  uint32_t lmin = kNoRank;
+  // ---- initial pair values: one probe per adjacent pair ----
+  uint32_t llim = kNoRank;                             // min limit() over my pairs
+  uint32_t lminv = kNoRank;                            // min value over my pairs
+  uint32_t firstv = kNoRank, lastv = kNoRank;          // values at my first / last slot
   {
     uint32_t x = ftok;
-    for (int e = 0; e < my_n; ++e) {
-      uint32_t y = (e + 1 < my_n) ? tok[(e + 1) * W + tid] : succ_tok;
-      uint32_t r = (y == kTokNone) ? kNoRank : probe_words(tab, x, y);
-      rnk[e * W + tid] = r;
-      lmin = min(lmin, r);
+    for (int k = 0; k < c; ++k) {
+      const uint32_t y = (k + 1 < c) ? T[(k + 1) * W + tid] : succ_tok;
+      const uint32_t v = (y == kTokNone) ? kNoRank : probe_words(tab, x, y);
+      V[k * W + tid] = v;
+      if (v != kNoRank) llim = min(llim, limit_of(v));
+      lminv = min(lminv, v);
+      if (k == 0) firstv = v;
+      lastv = v;
       x = y;
     }
   }
-  int buf = 0;
-  if (NW > 1) {
-    if (lane == 0) sh.wave_tok[wave] = ftok;           // lane 0 is empty only if the whole wave is
-    __syncthreads();
-  }
+
+  int buf = 0;                                         // which half of the double-buffered records is current
+  publish_record<NW>(sh, buf, wave, lane, c, llim, firstv, lastv, ftok);
 
   // ---- merge passes ----
   // Every pass removes at least one token, so n passes can never be needed; the bound only guarantees
   // that the loop ends whatever the memory contents.
-  int parity = 0;
   for (int pass = 0; pass < n; ++pass) {
-    const uint32_t r = block_min<NW>(lmin, sh, wave, parity);
-    parity ^= 1;
-    if (r == kNoRank) break;
-    const uint32_t merged = merged_token_word(r);
-    const bool self = (r & kFlagSelf) != 0;
-    const uint64_t ne = __ballot(mask != 0);           // non-empty lanes of my wave before this pass
+    // -- the horizon E of this pass and the boundary values from the neighbouring waves --
+    uint32_t E, wave_in_val = kNoRank, wave_nxt_val = kNoRank;
+    if (NW == 1) {
+      E = wave_reduce<OpMin>(llim);
+    } else {
+      __syncthreads();                                 // records of all waves are in place
+      const WaveRecord* rec = sh.rec + buf * NW;
+      E = kNoRank;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) E = min(E, rec[w].limit);
+      E = uniform(E);
+      for (int w = wave - 1; w >= 0; --w)              // nearest earlier non-empty wave
+        if (rec[w].first_tok != kTokNone) { wave_in_val = rec[w].last_val; break; }
+      for (int w = wave + 1; w < NW; ++w)              // nearest later non-empty wave
+        if (rec[w].first_tok != kTokNone) { wave_nxt_val = rec[w].first_val; break; }
+    }
+    if (E == kNoRank) break;                           // no pair of the string is in the table
+    // a pair is a candidate iff its value is below ev
+    const uint32_t ev = E >= 0xFFFFFu ? 0xFFFFFFFEu : (E << kRankShift);
 
-    uint32_t base = 0, start = 0;
-    if (self) {
-      // number the live tokens and find where the run that reaches each lane began
-      uint32_t total;
-      const uint32_t c = (uint32_t)pop_bits<mask_t>(mask);
-      base = block_scan_exclusive<NW, OpAdd>(c, sh, lane, wave, &total);
-      uint32_t z = c ? base + c : 0;                   // 1 + index of my last non-matching token
-      if (lmin == r) {
-        z = 0;
-        uint32_t g = base;
-        for (mask_t m = mask; m; m &= m - 1, ++g) {
-          const int e = ctz_bits<mask_t>(m);
-          if (rnk[e * W + tid] != r) z = g + 1;
+    // -- values just outside my column: the pair ending at my first token, the pair after my last --
+    const uint64_t ne = __ballot(c != 0);
+    const uint64_t below = ne & ((1ull << lane) - 1ull);
+    const uint64_t above = lane == 63 ? 0ull : (ne >> (lane + 1)) << (lane + 1);
+    uint32_t in_val = lane_read(lastv, below ? 63 - __builtin_clzll(below) : lane);
+    uint32_t nxt_val = lane_read(firstv, above ? __builtin_ctzll(above) : lane);
+    if (!below) in_val = wave_in_val;
+    if (!above) nxt_val = wave_nxt_val;
+
+    // A lane takes part in the pass if it holds a candidate or may lose its first token to one.
+    const bool active = c > 0 && (lminv < ev || in_val < ev);
+    const uint64_t active_lanes = __ballot(active);
+    const int kmax = (int)wave_reduce<OpMax>(active ? (uint32_t)c : 0u);
+
+    // -- walk 1: my element of the run-parity scan --
+    // A candidate is "beaten by its left" if the pair before it is a candidate of lower or equal rank.
+    uint32_t elem = c > 0 ? 2u : 0u;                   // inactive lane: its last pair restarts any run
+    if (active_lanes) {
+      if (active) {
+        uint32_t prev = in_val, par = 0, restart = 0;
+        for (int k = 0; k < kmax; ++k) {
+          if (k < c) {
+            const uint32_t cur = V[k * W + tid];
+            if (cur < ev && prev <= cur) par ^= 1u;
+            else { restart = 2u; par = 0; }
+            prev = cur;
+          }
+        }
+        elem = restart | par;
+      }
+    }
+    // parity of the run of beaten candidates that ends at the last live token before my column
+    uint32_t pin;
+    {
+      const uint32_t inc = wave_parity_scan(elem, lane);
+      uint32_t exc = (uint32_t)__shfl_up((int)inc, 1, 64);
+      if (lane == 0) exc = 0;
+      if (NW > 1) {
+        const uint32_t wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+        __syncthreads();                               // previous users of sh.part are done
+        if (lane == 0) sh.part[wave] = wave_total;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w) before = parity_combine(before, sh.part[w]);
+        exc = parity_combine(before, exc);
+      }
+      pin = exc & 1u;
+    }
+
+    // -- walk 2: decide, merge, and compact my column in place --
+    bool touched = false;                              // my tokens or my pair values changed
+    if (active_lanes) {
+      if (active) {
+        uint32_t prev = in_val, dlpar = pin;
+        uint32_t cur = V[tid];
+        // my first token is consumed if the pair ending at it is applied by the lane before me
+        bool skip = in_val < ev && !(cur < in_val) && pin == 0;
+        int o = 0;
+        bool prev_changed = false;
+        uint32_t prev_val = kNoRank;
+        for (int k = 0; k < kmax; ++k) {
+          if (k < c) {
+            const uint32_t nxt = (k + 1 < c) ? V[(k + 1) * W + tid] : nxt_val;
+            const bool cand = cur < ev;
+            dlpar = (cand && prev <= cur) ? (dlpar ^ 1u) : 0u;
+            const bool apply = cand && !(nxt < cur) && dlpar == 0;   // not beaten by its right, even place
+            if (!skip) {
+              const uint32_t t = apply ? merged_token_word(cur) : T[k * W + tid];
+              if (o > 0) V[(o - 1) * W + tid] = (prev_changed || apply) ? kDirty : prev_val;
+              T[o * W + tid] = t;
+              prev_changed = apply;
+              prev_val = cur;
+              ++o;
+            }
+            touched = touched || skip || apply;
+            skip = apply;                              // the right operand is consumed
+            prev = cur;
+            cur = nxt;
+          }
+        }
+        if (o > 0) V[(o - 1) * W + tid] = prev_changed ? kDirty : prev_val;
+        c = o;
+        if (touched) ftok = c > 0 ? T[tid] : kTokNone;
+      }
+    }
+
+    // -- who follows me now, and did the token there change? --
+    {
+      const uint64_t ne2 = __ballot(c != 0);
+      uint32_t next_wave_tok = kTokNone;
+      if (NW > 1) {
+        const uint32_t first = lane_read(ftok, ne2 ? __builtin_ctzll(ne2) : 0);
+        if (lane == 0) sh.first_tok[buf * NW + wave] = ne2 ? first : kTokNone;
+        __syncthreads();
+        for (int w = wave + 1; w < NW; ++w) {
+          const uint32_t t = sh.first_tok[buf * NW + w];
+          if (t != kTokNone) { next_wave_tok = t; break; }
         }
       }
-      start = block_scan_exclusive<NW, OpMax>(z, sh, lane, wave, &total);
-    }
-
-    mask_t dirty = 0;                                  // positions whose pair must be probed again
-    bool touched = false;                              // my tokens or liveness changed
-    bool cross = false;                                // I merged my last token with the next lane's first
-    if (lmin == r) {
-      uint32_t g = base;
-      const mask_t before = mask;
-      for (mask_t m = before; m; m &= m - 1, ++g) {
-        const int e = ctz_bits<mask_t>(m);
-        if (rnk[e * W + tid] != r) { start = g + 1; continue; }
-        if (self && ((g - start) & 1u)) continue;      // overlaps the occurrence to its left
-        // merge (token e, next live token) -> merged, kept at e
-        tok[e * W + tid] = merged;
-        const mask_t above = before & ~((((mask_t)2) << e) - 1);
-        if (above) mask &= ~((mask_t)1 << ctz_bits<mask_t>(above));
-        else cross = true;                             // the pair exists, so a following lane does
-        dirty |= (mask_t)1 << e;
-        const mask_t below = before & ((((mask_t)1) << e) - 1);
-        if (below) dirty |= (mask_t)1 << top_bit<mask_t>(below);
-        touched = true;
-      }
-    }
-
-    // ---- was my first live token merged into the lane before me? ----
-    const uint64_t crossmask = __ballot(cross);
-    uint32_t in_cross = 0;                             // the same question across the wave boundary
-    if (NW > 1) {
-      if (lane == 0) sh.wave_cross[wave] = ne ? (uint32_t)((crossmask >> (63 - __builtin_clzll(ne))) & 1) : 0u;
-      __syncthreads();
-      for (int w = wave - 1; w >= 0; --w) {            // nearest earlier wave that was non-empty
-        if (sh.wave_tok[buf * NW + w] != kTokNone) { in_cross = sh.wave_cross[w]; break; }
-      }
-    }
-    if (mask) {
-      const uint64_t below = ne & ((1ull << lane) - 1);
-      const uint32_t consumed = below ? (uint32_t)((crossmask >> (63 - __builtin_clzll(below))) & 1) : in_cross;
-      if (consumed) {
-        mask &= mask - 1;
-        touched = true;
-      }
-    }
-    if (touched) ftok = mask ? tok[ctz_bits<mask_t>(mask) * W + tid] : kTokNone;
-
-    // ---- who follows me now, and did the token there change? ----
-    const uint64_t ne2 = __ballot(mask != 0);
-    uint32_t next_wave_tok = kTokNone;
-    if (NW > 1) {
-      buf ^= 1;
-      const uint32_t first = (uint32_t)__shfl((int)ftok, ne2 ? __builtin_ctzll(ne2) : 0, 64);
-      if (lane == 0) sh.wave_tok[buf * NW + wave] = ne2 ? first : kTokNone;
-      __syncthreads();
-      for (int w = wave + 1; w < NW; ++w) {
-        const uint32_t t = sh.wave_tok[buf * NW + w];
-        if (t != kTokNone) { next_wave_tok = t; break; }
-      }
-    }
-    {
-      const uint64_t above = lane == 63 ? 0ull : (ne2 >> (lane + 1)) << (lane + 1);
-      uint32_t st = (uint32_t)__shfl((int)ftok, above ? __builtin_ctzll(above) : lane, 64);
-      if (!above) st = next_wave_tok;
-      if (mask && st != succ_tok) {
+      const uint64_t above2 = lane == 63 ? 0ull : (ne2 >> (lane + 1)) << (lane + 1);
+      uint32_t st = lane_read(ftok, above2 ? __builtin_ctzll(above2) : lane);
+      if (!above2) st = next_wave_tok;
+      if (c > 0 && st != succ_tok) {
         succ_tok = st;
-        dirty |= (mask_t)1 << top_bit<mask_t>(mask);
+        V[(c - 1) * W + tid] = kDirty;
+        touched = true;
       }
     }
 
-    // ---- probe the pairs that changed; refresh my minimum ----
-    if (dirty || touched) {
-      for (mask_t m = dirty & mask; m; m &= m - 1) {
-        const int e = ctz_bits<mask_t>(m);
-        const uint32_t x = tok[e * W + tid];
-        const mask_t above = mask & ~((((mask_t)2) << e) - 1);
-        const uint32_t y = above ? tok[ctz_bits<mask_t>(above) * W + tid] : succ_tok;
-        rnk[e * W + tid] = (y == kTokNone) ? kNoRank : probe_words(tab, x, y);
+    // -- look up the pairs that changed; refresh my summary --
+    if (__ballot(touched)) {
+      if (touched) {
+        llim = kNoRank;
+        lminv = kNoRank;
+        firstv = kNoRank;
+        lastv = kNoRank;
+        uint32_t x = ftok;
+        for (int k = 0; k < c; ++k) {
+          const uint32_t y = (k + 1 < c) ? T[(k + 1) * W + tid] : succ_tok;
+          uint32_t v = V[k * W + tid];
+          if (v == kDirty) {
+            v = (y == kTokNone) ? kNoRank : probe_words(tab, x, y);
+            V[k * W + tid] = v;
+          }
+          if (v != kNoRank) llim = min(llim, limit_of(v));
+          lminv = min(lminv, v);
+          if (k == 0) firstv = v;
+          lastv = v;
+          x = y;
+        }
       }
-      lmin = kNoRank;
-      for (mask_t m = mask; m; m &= m - 1) lmin = min(lmin, rnk[ctz_bits<mask_t>(m) * W + tid]);
     }
+    buf ^= 1;
+    publish_record<NW>(sh, buf, wave, lane, c, llim, firstv, lastv, ftok);
   }
 
   // ---- emit: prefix sum of live counts gives each lane's write index (section 4.3's compaction) ----
   uint32_t total;
-  const uint32_t c = (uint32_t)pop_bits<mask_t>(mask);
-  const uint32_t out0 = block_scan_exclusive<NW, OpAdd>(c, sh, lane, wave, &total);
+  const uint32_t out0 = block_prefix_sum<NW>((uint32_t)c, sh, lane, wave, &total);
   int32_t* dst = p.tmp_ids + begin + out0;
-  for (mask_t m = mask; m; m &= m - 1) *dst++ = (int32_t)(tok[ctz_bits<mask_t>(m) * W + tid] & kTokIdMask);
+  for (int k = 0; k < c; ++k) dst[k] = (int32_t)(T[k * W + tid] & kTokIdMask);
   if (tid == W - 1) p.counts[s] = (int32_t)total;
   block_sync<NW>();                                    // the LDS exchange arrays are reused by the next string
 }
@@ -365,18 +435,17 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   constexpr int W = NW * 64;
   extern __shared__ uint32_t smem[];
   uint32_t* cur = smem;
-  uint32_t *tok, *rnk;
+  uint32_t *T, *V;
   if (STAGED) {
-    tok = p.staged + (size_t)blockIdx.x * (2u * W * D);
-    rnk = tok + W * D;
+    T = p.staged + (size_t)blockIdx.x * (2u * W * D);
+    V = T + W * D;
   } else {
-    tok = cur; cur += W * D;
-    rnk = cur; cur += W * D;
+    T = cur; cur += W * D;
+    V = cur; cur += W * D;
   }
   BlockShared<NW> sh;
-  sh.wave_tok = cur; cur += 2 * NW;
-  sh.wave_cross = cur; cur += NW;
-  sh.red = cur; cur += 2 * NW;
+  sh.rec = (WaveRecord*)cur; cur += 2 * NW * (sizeof(WaveRecord) / sizeof(uint32_t));
+  sh.first_tok = cur; cur += 2 * NW;
   sh.part = cur; cur += NW;
   sh.item = cur;
 
@@ -384,7 +453,7 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   for (;;) {
     // Claim the next item.  Every lane of the first wave takes part in the atomic (lane 0 adds 1, the
     // others 0) so that no lane-dependent branch sits at the loop boundary: a branch on "thread 0" here,
-    // next to the "thread 0" store that ends the previous string, lets the compiler send the other lanes
+    // next to a single-lane store that ends the previous string, lets the compiler send the other lanes
     // round the loop on their own, past the lane-0 broadcast below.
     uint32_t claimed = 0;
     if (NW == 1) {
@@ -398,13 +467,13 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
     }
     const uint32_t item = uniform(claimed);            // lane 0's value, as a scalar
     if (item >= end) break;
-    encode_string<NW, D, STAGED>(p, (int)uniform((uint32_t)p.list[item]), tok, rnk, sh);
+    encode_string<NW, D, STAGED>(p, (int)uniform((uint32_t)p.list[item]), T, V, sh);
   }
 }
 
 template <int NW, int D, bool STAGED>
 constexpr size_t encode_lds_bytes() {
-  return sizeof(uint32_t) * ((STAGED ? 0 : 2 * NW * 64 * D) + 6 * NW + 4);
+  return sizeof(uint32_t) * ((STAGED ? 0 : 2 * NW * 64 * D) + 11 * NW + 4);
 }
 
 }  // namespace bpe
