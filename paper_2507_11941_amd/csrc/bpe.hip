@@ -19,7 +19,7 @@ struct bpe_table {
   int device = 0;
   int32_t n_merges = 0;
   int log2_buckets = 0;
-  void* d_mem = nullptr;          // buckets followed by the 256 byte token words
+  void* d_mem = nullptr;          // buckets, then the 256 byte token words, then the 256 x 256 byte-pair values
   size_t bucket_bytes = 0;
 };
 
@@ -182,7 +182,7 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
     const uint32_t bucket_mask = (uint32_t)n_buckets - 1;
     n_words = n_buckets * kSlotsPerBucket * 2;                 // uint32 words
     try {
-      host.assign(n_words + 256, 0xFFFFFFFFu);
+      host.assign(n_words + 256 + 65536, 0xFFFFFFFFu);
     } catch (const std::bad_alloc&) {
       return BPE_ENOMEM;
     }
@@ -198,6 +198,7 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
         code = horizon_encode((uint32_t)(first_use - r - 1));
       }
       const uint32_t value = make_value((uint32_t)r, code, fl >= 0, fr >= 0);
+      if (a < 256 && b < 256) host[n_words + 256 + (a << 8 | b)] = value;   // direct table for byte pairs
       const Placement pl = place_pair(a, b, log2_buckets);
       bool placed = false;
       for (uint32_t step = 0; step <= kMaxDisplacement && !placed; ++step) {
@@ -294,6 +295,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     EncodeParams p;
     p.table.buckets = (const uint4*)table->d_mem;
     p.table.byte_word = (const uint32_t*)((const char*)table->d_mem + table->bucket_bytes);
+    p.table.byte_pair = p.table.byte_word + 256;
     p.table.log2_buckets = table->log2_buckets;
     p.table.bucket_mask = ((uint32_t)1 << table->log2_buckets) - 1;
     p.bytes = bytes;
@@ -362,6 +364,17 @@ int bpe_read_profile(float* total_ms, int32_t* calls) {
   *calls = g_prof.used;
   return BPE_OK;
 }
+
+#ifdef BPE_TRACE
+int bpe_debug_trace(unsigned long long* out, int reset) {
+  if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_trace), sizeof(unsigned long long) * 32) != hipSuccess) return BPE_EHIP;
+  if (reset) {
+    unsigned long long zero[32] = {0};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(bpe::g_trace), zero, sizeof(zero)) != hipSuccess) return BPE_EHIP;
+  }
+  return BPE_OK;
+}
+#endif
 
 const char* bpe_strerror(int code) {
   switch (code) {
