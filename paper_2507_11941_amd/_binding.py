@@ -28,6 +28,11 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime under the same soname as the system one; whichever is loaded first
+    # serves the whole process.  Load torch's first so that the library shares the runtime (streams,
+    # device pointers) of the tensors it is handed.
+    import torch  # noqa: F401
+
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2507_11941_amd.build`")
     lib = ctypes.CDLL(_LIB_PATH)

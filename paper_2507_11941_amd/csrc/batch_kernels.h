@@ -33,7 +33,7 @@ __device__ inline int bin_key(int len, const TierPlan& plan) {
     if (len <= cap) {
       // bucket 0 holds the longest strings of the tier
       const int span = cap - lo;
-      int b = (int)(((int64_t)(cap - len) * kLenBuckets) / span);
+      int b = span > 0 ? (int)(((uint32_t)(cap - len) * (uint32_t)kLenBuckets) / (uint32_t)span) : 0;
       if (b >= kLenBuckets) b = kLenBuckets - 1;
       return t * kLenBuckets + b;
     }

@@ -2,6 +2,7 @@
 // batch encode.  Everything numeric happens in the kernels of encode_kernel.h / batch_kernels.h.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -31,7 +32,7 @@ namespace {
 
 struct Variant {
   int waves, depth;
-  bool staged;
+  bool staged, limits;            // per-position arrays in HBM instead of LDS; a third array holds the pair limits
   int capacity;                   // bytes
   size_t lds;
   const void* fn;
@@ -39,36 +40,58 @@ struct Variant {
   int max_grid = 0;               // resident workgroups on the whole device (filled on first use)
 };
 
-template <int NW, int D, bool ST>
+template <int NW, int D, bool ST, bool LIM>
 void launch_variant(const EncodeParams& p, int grid, hipStream_t stream) {
-  constexpr size_t lds = encode_lds_bytes<NW, D, ST>();
-  encode_kernel<NW, D, ST><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
+  constexpr size_t lds = encode_lds_bytes<NW, D, ST, LIM>();
+  encode_kernel<NW, D, ST, LIM><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
 }
 
-template <int NW, int D, bool ST>
+template <int NW, int D, bool ST, bool LIM>
 Variant make_variant() {
   Variant v;
   v.waves = NW;
   v.depth = D;
   v.staged = ST;
+  v.limits = LIM;
   v.capacity = 64 * NW * D;
-  v.lds = encode_lds_bytes<NW, D, ST>();
-  v.fn = (const void*)&encode_kernel<NW, D, ST>;
-  v.launch = &launch_variant<NW, D, ST>;
+  v.lds = encode_lds_bytes<NW, D, ST, LIM>();
+  v.fn = (const void*)&encode_kernel<NW, D, ST, LIM>;
+  v.launch = &launch_variant<NW, D, ST, LIM>;
   return v;
 }
 
 // Default plan: <= 1 KiB one wave, <= 4 KiB four waves, <= 16 KiB sixteen waves (all LDS-resident),
-// <= 64 KiB sixteen waves with the token arrays staged in HBM.
+// <= 64 KiB sixteen waves with the per-position arrays staged in HBM.
 Variant g_variants[kMaxTiers] = {
-    make_variant<1, 16, false>(),
-    make_variant<4, 16, false>(),
-    make_variant<16, 16, false>(),
-    make_variant<16, 64, true>(),
+    make_variant<1, 16, false, true>(),
+    make_variant<4, 16, false, true>(),
+    make_variant<16, 16, false, false>(),   // three arrays of 16 Ki words would not fit the 160 KB of LDS
+    make_variant<16, 64, true, true>(),
 };
+int g_tier_cap[kMaxTiers] = {0, 0, 0, 0};   // string-length bound of each tier (<= the variant's capacity)
 std::once_flag g_variants_once;
 int g_variants_status = BPE_OK;
 int g_num_cus = 0;
+
+std::once_flag g_caps_once;
+
+void init_caps() {
+  for (int t = 0; t < kMaxTiers; ++t) g_tier_cap[t] = g_variants[t].capacity;
+  // Tuning knob: BPE_TIER_CAPS="a,b,c,d" lowers the length bounds of the four variants (0 = variant unused),
+  // e.g. "0,4096,12288,65536" sends strings up to 1 KiB to the four-wave variant as well.
+  if (const char* env = std::getenv("BPE_TIER_CAPS")) {
+    int caps[kMaxTiers];
+    if (std::sscanf(env, "%d,%d,%d,%d", &caps[0], &caps[1], &caps[2], &caps[3]) == kMaxTiers) {
+      int prev = 0;
+      bool ok = true;
+      for (int t = 0; t < kMaxTiers; ++t) {
+        ok = ok && caps[t] >= prev && caps[t] <= g_variants[t].capacity;
+        prev = caps[t];
+      }
+      if (ok) for (int t = 0; t < kMaxTiers; ++t) g_tier_cap[t] = caps[t];
+    }
+  }
+}
 
 void init_variants() {
   int dev = 0;
@@ -96,15 +119,18 @@ void init_variants() {
 }
 
 int n_tiers_for(int32_t max_len) {
+  std::call_once(g_caps_once, init_caps);
   int n = 1;
-  while (n < kMaxTiers && g_variants[n - 1].capacity < max_len) ++n;
+  while (n < kMaxTiers && g_tier_cap[n - 1] < max_len) ++n;
   return n;
 }
 
 // Staged variant: resident workgroups each own one staging slab; the grid is capped so that the slabs
-// stay modest (each is 512 KiB for 64 KiB strings).
+// stay modest (each is 768 KiB for 64 KiB strings).
 constexpr int kMaxStagedGrid = 256;
-size_t staged_slab_bytes(const Variant& v) { return (size_t)2 * 64 * v.waves * v.depth * sizeof(uint32_t); }
+size_t staged_slab_bytes(const Variant& v) {
+  return (size_t)(v.limits ? 3 : 2) * 64 * v.waves * v.depth * sizeof(uint32_t);
+}
 
 constexpr size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -283,7 +309,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
 
   TierPlan plan;
   plan.n_tiers = n_tiers_for(max_len);
-  for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_variants[t].capacity;
+  for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_tier_cap[t];
 
   hipLaunchKernelGGL(zero_control_kernel, dim3(1), dim3(256), 0, stream, ctrl);
   if (batch > 0) {
@@ -366,6 +392,9 @@ int bpe_read_profile(float* total_ms, int32_t* calls) {
 }
 
 #ifdef BPE_TRACE
+int bpe_debug_dump(unsigned int* out) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_dbg), sizeof(unsigned int) * 64 * 16) == hipSuccess ? BPE_OK : BPE_EHIP;
+}
 int bpe_debug_trace(unsigned long long* out, int reset) {
   if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_trace), sizeof(unsigned long long) * 32) != hipSuccess) return BPE_EHIP;
   if (reset) {

@@ -33,6 +33,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "table_format.h"
 
@@ -242,10 +243,10 @@ __device__ inline uint32_t block_prefix_sum(uint32_t v, const BlockShared<NW>& s
 
 // My wave's record for the coming pass (no-op for a one-wave workgroup).
 template <int NW>
-__device__ inline void publish_record(const BlockShared<NW>& sh, int buf, int wave, int lane, int c,
+__device__ inline void publish_record(const BlockShared<NW>& sh, int buf, int wave, int lane, bool nonempty,
                                       uint32_t llim, uint32_t firstv, uint32_t lastv, uint32_t ftok) {
   if (NW == 1) return;
-  const uint64_t ne = __ballot(c != 0);
+  const uint64_t ne = __ballot(nonempty);
   const uint32_t wlim = wave_reduce<OpMin>(llim);
   const int fl = ne ? __builtin_ctzll(ne) : 0, ll = ne ? 63 - __builtin_clzll(ne) : 0;
   const uint32_t fv = lane_read(firstv, fl), ft = lane_read(ftok, fl), lv = lane_read(lastv, ll);
@@ -260,19 +261,26 @@ __device__ inline void publish_record(const BlockShared<NW>& sh, int buf, int wa
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Encode string s.  T/V: token words and pair values of each lane's live tokens, slot k of lane tid at
-// index k*W + tid, in LDS or (strings that exceed LDS) in HBM; every word is read and written by its
-// owning lane only.  V[k] is the value of the pair (token k, next live token of the string) -- for a
-// lane's last slot the next token is the first token of the next non-empty lane.
+// Encode string s.
 //
-// The per-lane loops run over chunks of kChunk slots: all loads of a chunk are issued before any is used,
-// so a lane pays one LDS (or L2) latency per chunk instead of one per slot; the work on a chunk is cut into
-// groups of kGroup slots that are skipped (scalar branch) once past the longest column of the wave.  D is a
-// multiple of kChunk, so a chunk never reads outside the arrays; slots at or beyond the lane's count hold
-// stale words that are loaded but never used.
+// T, V, L: token word, pair value and pair limit of every byte position of the string (L is kept only by
+// the variants with LIMITS; the others decode the limit from V when they need it); position k of lane
+// tid is word k*W + tid, in LDS or (strings that exceed LDS) in HBM.  Every word is read and written by its
+// owning lane only.  A position is live while its token exists; a merge keeps the merged token at the left
+// operand's position and kills the right one, so nothing ever moves.  V[k] is the value of the pair
+// (token k, next live token of the string) and L[k] its limit(); dead positions hold kNoRank in both.
+//
+// A pass costs every lane one sweep over its values (to find the candidates) and then work only per
+// candidate; loads are issued in chunks of kChunk positions, cut into groups of kGroup that are skipped
+// (scalar branch) beyond the string's bytes-per-lane.
+
+constexpr int kChunk = 16;
+constexpr int kGroup = 4;
+constexpr int kProbes = 4;     // table probes a lane keeps in flight
 
 #ifdef BPE_TRACE
 __device__ unsigned long long g_trace[32];
+__device__ unsigned int g_dbg[64 * 16];
 #define TRACE_T(var) const unsigned long long var = (blockIdx.x == 0) ? __builtin_readcyclecounter() : 0ull
 #define TRACE_ADD(slot, t0, t1) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[slot] += (t1) - (t0); } while (0)
 #else
@@ -280,29 +288,24 @@ __device__ unsigned long long g_trace[32];
 #define TRACE_ADD(slot, t0, t1)
 #endif
 
-constexpr int kChunk = 16;
-constexpr int kGroup = 4;
-constexpr int kProbes = 4;     // table probes a lane keeps in flight
+template <class M> __device__ inline int ctz_bits(M m);
+template <> __device__ inline int ctz_bits<uint32_t>(uint32_t m) { return __builtin_ctz(m); }
+template <> __device__ inline int ctz_bits<uint64_t>(uint64_t m) { return __builtin_ctzll(m); }
+template <class M> __device__ inline int top_bit(M m);
+template <> __device__ inline int top_bit<uint32_t>(uint32_t m) { return 31 - __builtin_clz(m); }
+template <> __device__ inline int top_bit<uint64_t>(uint64_t m) { return 63 - __builtin_clzll(m); }
+template <class M> __device__ inline int pop_bits(M m);
+template <> __device__ inline int pop_bits<uint32_t>(uint32_t m) { return __builtin_popcount(m); }
+template <> __device__ inline int pop_bits<uint64_t>(uint64_t m) { return __builtin_popcountll(m); }
+template <class M> __device__ inline M bit_at(int k) { return (M)1 << k; }
+template <class M> __device__ inline M bits_below(int k) { return ((M)1 << k) - 1; }            // k < width
+template <class M> __device__ inline M bits_above(int k) { return ~((((M)2) << k) - 1); }        // k < width
 
-// Per-lane summary of its column, kept in registers between passes.
-struct LaneState {
-  int c = 0;                         // live tokens
-  uint32_t ftok = kTokNone;          // first live token word
-  uint32_t succ_tok = kTokNone;      // the token my last pair is looked up against
-  uint32_t firstv = kNoRank;         // pair value at slot 0
-  uint32_t lastv = kNoRank;          // pair value at slot c-1
-  uint32_t rest_lim = kNoRank;       // min limit() over slots 0..c-2
-  uint32_t rest_minv = kNoRank;      // min value over slots 0..c-2
-  __device__ uint32_t lim() const {
-    return min(rest_lim, (c > 0 && lastv != kNoRank) ? limit_of(lastv) : kNoRank);
-  }
-  __device__ uint32_t minv() const { return c > 0 ? min(rest_minv, lastv) : kNoRank; }
-};
-
-template <int NW, int D, bool STAGED>
+template <int NW, int D, bool STAGED, bool LIMITS>
 __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict__ T, uint32_t* __restrict__ V,
-                              const BlockShared<NW>& sh) {
-  static_assert(D % kChunk == 0 && D <= 64, "chunks must tile the column; dirty slots are a 64-bit mask");
+                              uint32_t* __restrict__ L, const BlockShared<NW>& sh) {
+  static_assert(D % kGroup == 0 && D <= 64, "groups must tile the column; positions are a 64-bit mask at most");
+  using mask_t = typename std::conditional<(D <= 32), uint32_t, uint64_t>::type;
   constexpr int W = NW * 64;
   const int tid = (int)threadIdx.x;
   const int lane = tid & 63;
@@ -315,43 +318,50 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     if (tid == W - 1) p.counts[s] = 0;
     return;
   }
-  const uint8_t* src = p.bytes + begin;
-  const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D
   TRACE_T(t_start);
-  LaneState me;
-  me.c = n - tid * d;
-  me.c = me.c < 0 ? 0 : (me.c > d ? d : me.c);
+  const uint8_t* src = p.bytes + begin;
+  const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D (uniform)
+  const int dpad = (d + kGroup - 1) / kGroup * kGroup; // the sweeps read whole groups: pad with dead positions
+  int c0 = n - tid * d;                                // my byte count
+  c0 = c0 < 0 ? 0 : (c0 > d ? d : c0);
+
+  mask_t live = c0 >= (int)(8 * sizeof(mask_t)) ? ~(mask_t)0 : bits_below<mask_t>(c0);
+  uint32_t ftok = kTokNone;                            // my first live token word
+  uint32_t succ_tok = kTokNone;                        // the token my last pair is looked up against
+  uint32_t firstv = kNoRank, lastv = kNoRank;          // pair values at my first / last live position
+  uint32_t llim = kNoRank;                             // min of L over my positions
 
   // ---- load: byte-level pre-tokenisation (section 4.1), id = byte value; and the initial pair values,
   //      one lookup per adjacent byte pair in the direct 256 x 256 table ----
   {
     const int base = tid * d;
-    const int c = me.c;
     for (int k0 = 0; k0 < d; k0 += kChunk) {           // d is uniform: no lane leaves the loop early
       uint32_t b[kChunk + 1];
 #pragma unroll
       for (int j = 0; j <= kChunk; ++j) {
         const int i = base + k0 + j;
-        b[j] = (k0 + j <= c && i < n) ? src[i] : 0x100u;   // 0x100: no such byte
+        b[j] = (k0 + j <= c0 && i < n) ? src[i] : 0x100u;   // 0x100: no such byte
       }
       uint32_t v[kChunk];
 #pragma unroll
       for (int j = 0; j < kChunk; ++j)
-        v[j] = (k0 + j < c && b[j + 1] < 0x100u) ? tab.byte_pair[(b[j] << 8) | b[j + 1]] : kNoRank;
+        v[j] = (k0 + j < c0 && b[j + 1] < 0x100u) ? tab.byte_pair[(b[j] << 8) | b[j + 1]] : kNoRank;
 #pragma unroll
       for (int j = 0; j < kChunk; ++j) {
         const int k = k0 + j;
-        if (k < c) {
-          const uint32_t w = sh.byte_word[b[j]];
-          T[k * W + tid] = w;
+        if (k < dpad) {                                // positions from c0 on are dead from the start
+          const uint32_t lim = v[j] != kNoRank ? limit_of(v[j]) : kNoRank;
           V[k * W + tid] = v[j];
-          if (k == 0) { me.ftok = w; me.firstv = v[j]; }
-          if (k == c - 1) {
-            me.lastv = v[j];
-            if (b[j + 1] < 0x100u) me.succ_tok = sh.byte_word[b[j + 1]];
-          } else {
-            if (v[j] != kNoRank) me.rest_lim = min(me.rest_lim, limit_of(v[j]));
-            me.rest_minv = min(me.rest_minv, v[j]);
+          if (LIMITS) L[k * W + tid] = lim;
+          llim = min(llim, lim);
+          if (k < c0) {
+            const uint32_t w = sh.byte_word[b[j]];
+            T[k * W + tid] = w;
+            if (k == 0) { ftok = w; firstv = v[j]; }
+            if (k == c0 - 1) {
+              lastv = v[j];
+              if (b[j + 1] < 0x100u) succ_tok = sh.byte_word[b[j + 1]];
+            }
           }
         }
       }
@@ -359,7 +369,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
   }
 
   int buf = 0;                                         // which half of the double-buffered exchange is current
-  publish_record<NW>(sh, buf, wave, lane, me.c, me.lim(), me.firstv, me.lastv, me.ftok);
+  publish_record<NW>(sh, buf, wave, lane, live != 0, llim, firstv, lastv, ftok);
   TRACE_T(t_loaded);
   TRACE_ADD(0, t_start, t_loaded);
 
@@ -371,7 +381,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     // -- the horizon E of this pass and the boundary values from the neighbouring waves --
     uint32_t E, wave_in_val = kNoRank, wave_nxt_val = kNoRank;
     if (NW == 1) {
-      E = wave_reduce<OpMin>(me.lim());
+      E = wave_reduce<OpMin>(llim);
     } else {
       __syncthreads();                                 // records of all waves are in place
       const WaveRecord* rec = sh.rec + buf * NW;
@@ -389,56 +399,85 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     const uint32_t ev = E >= 0xFFFFFu ? 0xFFFFFFFEu : (E << kRankShift);
 
     // -- values just outside my column: the pair ending at my first token, the pair after my last --
-    const uint64_t ne = __ballot(me.c != 0);
+    const uint64_t ne = __ballot(live != 0);
     const uint64_t below = ne & ((1ull << lane) - 1ull);
     const uint64_t above = lane == 63 ? 0ull : (ne >> (lane + 1)) << (lane + 1);
-    uint32_t in_val = lane_read(me.lastv, below ? 63 - __builtin_clzll(below) : lane);
-    uint32_t nxt_val = lane_read(me.firstv, above ? __builtin_ctzll(above) : lane);
+    uint32_t in_val = lane_read(lastv, below ? 63 - __builtin_clzll(below) : lane);
+    uint32_t nxt_val = lane_read(firstv, above ? __builtin_ctzll(above) : lane);
     if (!below) in_val = wave_in_val;
     if (!above) nxt_val = wave_nxt_val;
-
-    // A lane takes part in the pass if it holds a candidate or may lose its first token to one.
-    const bool active = me.c > 0 && (me.minv() < ev || in_val < ev);
-    const uint64_t active_lanes = __ballot(active);
-    const int kmax = (int)wave_reduce<OpMax>(active ? (uint32_t)me.c : 0u);
-
-    uint64_t dirty = 0;                                // slots whose pair must be looked up again
-    uint32_t pin = 0;
     TRACE_T(t1);
     TRACE_ADD(1, t0, t1);
-    // -- walk 1: my element of the run-parity scan --
-    // A candidate is "beaten by its left" if the pair before it is a candidate of lower or equal rank.
-    uint32_t elem = me.c > 0 ? 2u : 0u;                // inactive lane: its last pair restarts any run
-    if (active_lanes) {
-      uint32_t prev = in_val, par = 0, restart = 0;
-      for (int k0 = 0; k0 < kmax; k0 += kChunk) {
-        uint32_t v[kChunk];
+
+    // -- sweep: which of my pairs are candidates --
+    mask_t cm = 0;
+    for (int k0 = 0; k0 < d; k0 += kChunk) {
+      uint32_t v[kChunk];
 #pragma unroll
-        for (int g = 0; g < kChunk; g += kGroup) {
-          if (k0 + g < kmax) {
+      for (int g = 0; g < kChunk; g += kGroup) {
+        if (g < D && k0 + g < d) {
 #pragma unroll
-            for (int j = g; j < g + kGroup; ++j) v[j] = V[(k0 + j) * W + tid];
-          }
-        }
-#pragma unroll
-        for (int g = 0; g < kChunk; g += kGroup) {
-          if (k0 + g < kmax) {
-#pragma unroll
-            for (int j = g; j < g + kGroup; ++j) {
-              if (active && k0 + j < me.c) {
-                if (v[j] < ev && prev <= v[j]) par ^= 1u;
-                else { restart = 2u; par = 0; }
-                prev = v[j];
-              }
-            }
-          }
+          for (int j = g; j < g + kGroup; ++j) v[j] = V[(k0 + j) * W + tid];
         }
       }
-      if (active) elem = restart | par;
+#pragma unroll
+      for (int g = 0; g < kChunk; g += kGroup) {
+        if (g < D && k0 + g < d) {
+#pragma unroll
+          for (int j = g; j < g + kGroup; ++j) cm |= (mask_t)(v[j] < ev ? 1u : 0u) << (k0 + j);
+        }
+      }
     }
     TRACE_T(t2);
     TRACE_ADD(2, t1, t2);
-    // parity of the run of beaten candidates that ends at the last live token before my column
+
+    // -- walk 1 over my candidates: which are beaten by a neighbour, and my element of the parity scan --
+    // A candidate is "beaten by its left" if the pair before it is a candidate of lower or equal rank, and
+    // "beaten by its right" if the pair after it is a candidate of strictly lower rank.  Going right along
+    // a run of left-beaten candidates the applied ones alternate, starting with the run's unbeaten head.
+    // e0: candidates at an even place of their run, counting as if the run that reaches my first position
+    //     (mask lr) started there; nbr: candidates not beaten by their right.
+    mask_t e0 = 0, lr = 0, nbr = 0;
+    uint32_t elem = live ? 2u : 0u;                    // no trailing run: my last pair restarts the count
+    if (__ballot(cm != 0)) {
+      int prevc = -1;
+      uint32_t prevv = 0, prev_dl = 0;
+      bool prev_lead = false, prev_bl = false;
+      for (mask_t m = cm; m; m &= m - 1) {
+        const int k = ctz_bits<mask_t>(m);
+        const uint32_t v = V[k * W + tid];
+        const mask_t lower = live & bits_below<mask_t>(k);
+        bool bl, lead;
+        uint32_t dl;
+        if (lower) {
+          const bool adjacent = top_bit<mask_t>(lower) == prevc;   // the live position before k is a candidate
+          bl = adjacent && prevv <= v;
+          if (prevc >= 0 && !(adjacent && v < prevv)) nbr |= bit_at<mask_t>(prevc);
+          dl = bl ? (prev_dl ^ 1u) : 0u;
+          lead = bl && prev_lead;
+        } else {                                       // k is my first live position
+          bl = in_val <= v;                            // v is a candidate, so in_val is one too
+          dl = bl ? 1u : 0u;
+          lead = bl;
+        }
+        if (dl == 0) e0 |= bit_at<mask_t>(k);
+        if (lead) lr |= bit_at<mask_t>(k);
+        prevc = k;
+        prevv = v;
+        prev_dl = dl;
+        prev_lead = lead;
+        prev_bl = bl;
+      }
+      if (prevc >= 0) {
+        const bool is_last = (live & bits_above<mask_t>(prevc)) == 0;
+        if (!(is_last && nxt_val < prevv)) nbr |= bit_at<mask_t>(prevc);
+        if (is_last && prev_bl) elem = (prev_lead ? 0u : 2u) | prev_dl;
+      }
+    }
+    TRACE_T(t3);
+    TRACE_ADD(3, t2, t3);
+    // parity of the run of left-beaten candidates that ends at the last live token before my column
+    uint32_t pin;
     {
       const uint32_t inc = wave_scan<OpParity>(elem, 0u);
       uint32_t exc = wave_shift_up(inc, 0u);
@@ -452,95 +491,56 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
       }
       pin = exc & 1u;
     }
-
-    TRACE_T(t3);
-    TRACE_ADD(3, t2, t3);
-    // -- walk 2: decide, merge, and compact my column in place --
-    if (active_lanes) {
-      const int c = me.c;
-      uint32_t prev = in_val, dlpar = pin;
-      uint32_t cur = active ? V[tid] : kNoRank;
-      // my first token is consumed if the pair ending at it is applied by the lane before me
-      bool skip = active && in_val < ev && !(cur < in_val) && pin == 0;
-      int o = 0;
-      bool prev_changed = false, touched = false;
-      uint32_t prev_val = kNoRank;
-      uint32_t rest_lim = kNoRank, rest_minv = kNoRank, firstv = kNoRank;
-      for (int k0 = 0; k0 < kmax; k0 += kChunk) {
-        uint32_t vn[kChunk], tk[kChunk];
-#pragma unroll
-        for (int g = 0; g < kChunk; g += kGroup) {
-          if (k0 + g < kmax) {
-#pragma unroll
-            for (int j = g; j < g + kGroup; ++j) {
-              const int kn = k0 + j + 1;
-              vn[j] = V[(kn < D ? kn : D - 1) * W + tid];
-              tk[j] = T[(k0 + j) * W + tid];
-            }
-          }
-        }
-#pragma unroll
-        for (int g = 0; g < kChunk; g += kGroup) {
-          if (k0 + g < kmax) {
-#pragma unroll
-            for (int j = g; j < g + kGroup; ++j) {
-              const int k = k0 + j;
-              if (active && k < c) {
-                const uint32_t nxt = (k + 1 < c) ? vn[j] : nxt_val;
-                const bool cand = cur < ev;
-                dlpar = (cand && prev <= cur) ? (dlpar ^ 1u) : 0u;
-                const bool apply = cand && !(nxt < cur) && dlpar == 0;   // not beaten by its right, even place
-                if (!skip) {
-                  if (o > 0) {                         // the slot before is now known not to be the last
-                    const bool dty = prev_changed || apply;
-                    V[(o - 1) * W + tid] = dty ? kDirty : prev_val;
-                    if (dty) {
-                      dirty |= 1ull << (o - 1);
-                    } else {
-                      if (prev_val != kNoRank) rest_lim = min(rest_lim, limit_of(prev_val));
-                      rest_minv = min(rest_minv, prev_val);
-                    }
-                    if (o == 1) firstv = dty ? kDirty : prev_val;
-                  }
-                  T[o * W + tid] = apply ? merged_token_word(cur) : tk[j];
-                  prev_changed = apply;
-                  prev_val = cur;
-                  ++o;
-                }
-                touched = touched || skip || apply;
-                skip = apply;                          // the right operand is consumed
-                prev = cur;
-                cur = nxt;
-              }
-            }
-          }
-        }
-      }
-      if (active) {
-        if (o > 0) {                                   // the last slot: its pair crosses into the next lane
-          V[(o - 1) * W + tid] = prev_changed ? kDirty : prev_val;
-          if (prev_changed) dirty |= 1ull << (o - 1);
-          me.lastv = prev_changed ? kDirty : prev_val;
-          if (o == 1) firstv = me.lastv;
-        } else {
-          me.lastv = kNoRank;
-        }
-        me.c = o;
-        me.firstv = firstv;
-        me.rest_lim = rest_lim;
-        me.rest_minv = rest_minv;
-        if (touched) me.ftok = o > 0 ? T[tid] : kTokNone;
-      }
-    }
-
     TRACE_T(t4);
     TRACE_ADD(4, t3, t4);
+
+    // -- walk 2 over the candidates that are applied: merge --
+    const mask_t applied = cm & nbr & (pin ? (e0 ^ lr) : e0);
+    // my first token is consumed if the pair ending at it is applied by the lane before me
+    const bool skip_first = live != 0 && in_val < ev && !(firstv < in_val) && pin == 0;
+    const bool touched = skip_first || applied != 0;
+#ifdef BPE_TRACE
+    if (blockIdx.x == 0 && pass == 0 && tid < 64) {
+      unsigned int* q = g_dbg + tid * 16;
+      q[0] = (unsigned)live; q[1] = (unsigned)cm; q[2] = elem; q[3] = pin; q[4] = in_val; q[5] = nxt_val;
+      q[6] = (unsigned)e0; q[7] = (unsigned)lr; q[8] = (unsigned)nbr; q[9] = (unsigned)applied; q[10] = skip_first;
+      q[11] = firstv; q[12] = lastv; q[13] = ev; q[14] = llim; q[15] = (unsigned)d;
+    }
+#endif
+    mask_t dirty = 0;                                  // positions whose pair must be looked up again
+    if (__ballot(touched)) {
+      for (mask_t m = applied; m; m &= m - 1) {
+        const int k = ctz_bits<mask_t>(m);
+        T[k * W + tid] = merged_token_word(V[k * W + tid]);
+        const mask_t upper = live & bits_above<mask_t>(k);
+        if (upper) {                                   // the right operand is mine: it dies
+          const int kn = ctz_bits<mask_t>(upper);
+          live &= ~bit_at<mask_t>(kn);
+          V[kn * W + tid] = kNoRank;
+          if (LIMITS) L[kn * W + tid] = kNoRank;
+        }                                              // else it is the next lane's first token (skip_first there)
+        dirty |= bit_at<mask_t>(k);
+        const mask_t lower = live & bits_below<mask_t>(k);
+        if (lower) dirty |= bit_at<mask_t>(top_bit<mask_t>(lower));
+      }
+      if (skip_first) {
+        const int f = ctz_bits<mask_t>(live);
+        live &= ~bit_at<mask_t>(f);
+        V[f * W + tid] = kNoRank;
+        if (LIMITS) L[f * W + tid] = kNoRank;
+      }
+      dirty &= live;
+      if (touched) ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
+    }
+    TRACE_T(t5);
+    TRACE_ADD(5, t4, t5);
+
     // -- who follows me now, and did the token there change? --
     {
-      const uint64_t ne2 = __ballot(me.c != 0);
+      const uint64_t ne2 = __ballot(live != 0);
       uint32_t next_wave_tok = kTokNone;
       if (NW > 1) {
-        const uint32_t first = lane_read(me.ftok, ne2 ? __builtin_ctzll(ne2) : 0);
+        const uint32_t first = lane_read(ftok, ne2 ? __builtin_ctzll(ne2) : 0);
         if (lane == 0) sh.first_tok[buf * NW + wave] = ne2 ? first : kTokNone;
         __syncthreads();
         for (int w = wave + 1; w < NW; ++w) {
@@ -549,103 +549,110 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         }
       }
       const uint64_t above2 = lane == 63 ? 0ull : (ne2 >> (lane + 1)) << (lane + 1);
-      uint32_t st = lane_read(me.ftok, above2 ? __builtin_ctzll(above2) : lane);
+      uint32_t st = lane_read(ftok, above2 ? __builtin_ctzll(above2) : lane);
       if (!above2) st = next_wave_tok;
-      if (me.c > 0 && st != me.succ_tok) {
-        me.succ_tok = st;
-        dirty |= 1ull << (me.c - 1);
+      if (live != 0 && st != succ_tok) {
+        succ_tok = st;
+        dirty |= bit_at<mask_t>(top_bit<mask_t>(live));
       }
     }
+    TRACE_T(t6);
+    TRACE_ADD(6, t5, t6);
 
-    TRACE_T(t5);
-    TRACE_ADD(5, t4, t5);
-    // -- look up the pairs that changed, kProbes at a time --
+    // -- look up the pairs that changed, kProbes at a time; refresh my summary --
+    const bool refresh = touched || dirty != 0;
     while (__ballot(dirty != 0)) {
-      TRACE_ADD(9, 0ull, 1ull);
       int k[kProbes];
       uint32_t x[kProbes], y[kProbes];
       ProbeInFlight f[kProbes];
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) {
         k[j] = -1;
+        x[j] = 0;
+        y[j] = kTokNone;
         if (dirty) {
-          k[j] = __builtin_ctzll(dirty);
+          k[j] = ctz_bits<mask_t>(dirty);
           dirty &= dirty - 1;
           x[j] = T[k[j] * W + tid];
-          y[j] = T[(k[j] + 1 < D ? k[j] + 1 : D - 1) * W + tid];
+          const mask_t upper = live & bits_above<mask_t>(k[j]);
+          y[j] = upper ? T[ctz_bits<mask_t>(upper) * W + tid] : succ_tok;
         }
       }
 #pragma unroll
-      for (int j = 0; j < kProbes; ++j) {
-        const uint32_t yy = (k[j] + 1 < me.c) ? y[j] : me.succ_tok;
-        probe_start(tab, x[j], yy, k[j] >= 0, f[j]);
-      }
+      for (int j = 0; j < kProbes; ++j) probe_start(tab, x[j], y[j], k[j] >= 0, f[j]);
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) {
         if (k[j] >= 0) {
           const uint32_t v = probe_finish(tab, f[j]);
           V[k[j] * W + tid] = v;
-          if (k[j] == 0) me.firstv = v;
-          if (k[j] == me.c - 1) {
-            me.lastv = v;
-          } else {
-            if (v != kNoRank) me.rest_lim = min(me.rest_lim, limit_of(v));
-            me.rest_minv = min(me.rest_minv, v);
-          }
+          if (LIMITS) L[k[j] * W + tid] = v != kNoRank ? limit_of(v) : kNoRank;
         }
       }
     }
+    TRACE_T(t7);
+    TRACE_ADD(7, t6, t7);
+    if (__ballot(refresh)) {
+      uint32_t m = kNoRank;
+      for (int k0 = 0; k0 < d; k0 += kChunk) {
+        uint32_t l[kChunk];
+#pragma unroll
+        for (int g = 0; g < kChunk; g += kGroup) {
+          if (g < D && k0 + g < d) {
+#pragma unroll
+            for (int j = g; j < g + kGroup; ++j) l[j] = LIMITS ? L[(k0 + j) * W + tid] : V[(k0 + j) * W + tid];
+          }
+        }
+#pragma unroll
+        for (int g = 0; g < kChunk; g += kGroup) {
+          if (g < D && k0 + g < d) {
+#pragma unroll
+            for (int j = g; j < g + kGroup; ++j)
+              m = min(m, LIMITS ? l[j] : (l[j] != kNoRank ? limit_of(l[j]) : kNoRank));
+          }
+        }
+      }
+      if (refresh) {
+        llim = m;
+        firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
+        lastv = live ? V[top_bit<mask_t>(live) * W + tid] : kNoRank;
+      }
+    }
     buf ^= 1;
-    publish_record<NW>(sh, buf, wave, lane, me.c, me.lim(), me.firstv, me.lastv, me.ftok);
-    TRACE_T(t6);
-    TRACE_ADD(6, t5, t6);
-    TRACE_ADD(8, 0ull, 1ull);
+    publish_record<NW>(sh, buf, wave, lane, live != 0, llim, firstv, lastv, ftok);
+    TRACE_T(t8);
+    TRACE_ADD(8, t7, t8);
+    TRACE_ADD(10, 0ull, 1ull);
   }
   TRACE_T(t_passes);
 
   // ---- emit: prefix sum of live counts gives each lane's write index (section 4.3's compaction) ----
   uint32_t total;
-  const uint32_t out0 = block_prefix_sum<NW>((uint32_t)me.c, sh, lane, wave, &total);
+  const uint32_t out0 = block_prefix_sum<NW>((uint32_t)pop_bits<mask_t>(live), sh, lane, wave, &total);
   int32_t* dst = p.tmp_ids + begin + out0;
-  const int cmax = (int)wave_reduce<OpMax>((uint32_t)me.c);
-  for (int k0 = 0; k0 < cmax; k0 += kChunk) {
-    uint32_t t[kChunk];
-#pragma unroll
-    for (int g = 0; g < kChunk; g += kGroup) {
-      if (k0 + g < cmax) {
-#pragma unroll
-        for (int j = g; j < g + kGroup; ++j) t[j] = T[(k0 + j) * W + tid];
-      }
-    }
-#pragma unroll
-    for (int g = 0; g < kChunk; g += kGroup) {
-      if (k0 + g < cmax) {
-#pragma unroll
-        for (int j = g; j < g + kGroup; ++j)
-          if (k0 + j < me.c) dst[k0 + j] = (int32_t)(t[j] & kTokIdMask);
-      }
-    }
-  }
+  for (mask_t m = live; m; m &= m - 1) *dst++ = (int32_t)(T[ctz_bits<mask_t>(m) * W + tid] & kTokIdMask);
   if (tid == W - 1) p.counts[s] = (int32_t)total;
   block_sync<NW>();                                    // the LDS exchange arrays are reused by the next string
   TRACE_T(t_end);
-  TRACE_ADD(7, t_passes, t_end);
-  TRACE_ADD(10, t_start, t_end);
+  TRACE_ADD(9, t_passes, t_end);
+  TRACE_ADD(11, t_start, t_end);
 }
 
 // Persistent workgroups: each claims the next string of its tier until the tier's list is exhausted.
-template <int NW, int D, bool STAGED>
+template <int NW, int D, bool STAGED, bool LIMITS>
 __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   constexpr int W = NW * 64;
   extern __shared__ uint32_t smem[];
   uint32_t* cur = smem;
-  uint32_t *T, *V;
+  uint32_t *T, *V, *L;
   if (STAGED) {
-    T = p.staged + (size_t)blockIdx.x * (2u * W * D);
+    T = p.staged + (size_t)blockIdx.x * ((LIMITS ? 3u : 2u) * W * D);
     V = T + W * D;
+    L = V + W * D;
   } else {
     T = cur; cur += W * D;
     V = cur; cur += W * D;
+    L = cur;
+    if (LIMITS) cur += W * D;
   }
   BlockShared<NW> sh;
   sh.rec = (WaveRecord*)cur; cur += 2 * NW * (sizeof(WaveRecord) / sizeof(uint32_t));
@@ -675,13 +682,13 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
     }
     const uint32_t item = uniform(claimed);            // lane 0's value, as a scalar
     if (item >= end) break;
-    encode_string<NW, D, STAGED>(p, (int)uniform((uint32_t)p.list[item]), T, V, sh);
+    encode_string<NW, D, STAGED, LIMITS>(p, (int)uniform((uint32_t)p.list[item]), T, V, L, sh);
   }
 }
 
-template <int NW, int D, bool STAGED>
+template <int NW, int D, bool STAGED, bool LIMITS>
 constexpr size_t encode_lds_bytes() {
-  return sizeof(uint32_t) * ((STAGED ? 0 : 2 * NW * 64 * D) + 12 * NW + 4 + 256);
+  return sizeof(uint32_t) * ((STAGED ? 0 : (LIMITS ? 3 : 2) * NW * 64 * D) + 12 * NW + 4 + 256);
 }
 
 }  // namespace bpe
