@@ -22,6 +22,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E peak, GB/s
 
 
+def measured_traffic(config: int):
+    """HBM-side bytes per encode-kernel launch from the committed rocprofv3 counter summary, if there is one
+    for this workload (the counters cannot be read from inside this process)."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", f"encode_kernel_config{config}_pmc.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None
+    return int(m.group(1)) if m else None
+
+
 def cpu_baseline(merges, data, offsets, target_seconds=2.5):
     """The oracle's textbook sequential encoder on all host threads, on repetitions of the same batch."""
     import oracle
@@ -55,6 +68,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device copy (a kernel of known traffic for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: strings are independent, so more GPUs only split the batch; "
@@ -89,6 +105,13 @@ def main() -> int:
 
     def step():
         bpe.encode_batch(table, d_data, d_off, max_len, out_ids, out_off, ws, stream)
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -132,7 +155,7 @@ def main() -> int:
                    "batch": batch, "input_bytes": total, "max_len": max_len, "tokens": n_tokens},
         "hbm_fraction_input": total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "encode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config),
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": kernel_ms,
                      "kernel_calls_timed": kernel_calls},
     }

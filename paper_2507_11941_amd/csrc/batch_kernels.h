@@ -19,9 +19,6 @@ struct TierPlan {
 
 // Control block at the start of the workspace.
 struct Control {
-  uint32_t hist[kBinKeys];                           // strings per (tier, length bucket)
-  uint32_t key_base[kBinKeys + 1];                   // exclusive scan of hist
-  uint32_t cursor[kBinKeys];                         // scatter cursors
   uint32_t tier_base[kMaxTiers + 1];                 // start of each tier's slice of the list
   uint32_t queue_head[kMaxTiers];                    // work-queue heads of the encode kernels
 };
@@ -42,48 +39,40 @@ __device__ inline int bin_key(int len, const TierPlan& plan) {
   return -1;                                         // longer than any launched variant: skipped
 }
 
-__global__ void zero_control_kernel(Control* c) {
-  uint32_t* w = (uint32_t*)c;
-  for (int i = threadIdx.x; i < (int)(sizeof(Control) / 4); i += blockDim.x) w[i] = 0;
-}
-
-__global__ void bin_count_kernel(const int64_t* offsets, int batch, TierPlan plan, Control* c,
-                                 int32_t* counts) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= batch) return;
-  const int64_t len = offsets[s + 1] - offsets[s];
-  const int key = (len < 0 || len > 0x7FFFFFFF) ? -1 : bin_key((int)len, plan);
-  if (key >= 0) atomicAdd(&c->hist[key], 1u);
-  else counts[s] = 0;                                // never encoded: contributes no tokens
-}
-
-__global__ void bin_scan_kernel(Control* c, int n_tiers) {
-  // kBinKeys = 256 keys, one thread each
-  __shared__ uint32_t tmp[kBinKeys];
+// One workgroup bins the whole batch: histogram of (class, length bucket) keys in LDS, exclusive scan of the
+// 256 keys, then the scatter of string indices into the work list (class-major, longest bucket first).
+// Also resets the work-queue heads.  A second pass over the offsets is cheaper than a second launch.
+__global__ __launch_bounds__(1024) void bin_kernel(const int64_t* offsets, int batch, TierPlan plan, Control* c,
+                                                   int32_t* list, int32_t* counts) {
+  __shared__ uint32_t hist[kBinKeys], scan[kBinKeys], cursor[kBinKeys];
   const int t = threadIdx.x;
-  tmp[t] = c->hist[t];
+  if (t < kBinKeys) { hist[t] = 0; cursor[t] = 0; }
   __syncthreads();
-  for (int step = 1; step < kBinKeys; step <<= 1) {
-    uint32_t v = t >= step ? tmp[t - step] : 0;
+  for (int s = t; s < batch; s += 1024) {
+    const int64_t len = offsets[s + 1] - offsets[s];
+    const int key = (len < 0 || len > 0x7FFFFFFF) ? -1 : bin_key((int)len, plan);
+    if (key >= 0) atomicAdd(&hist[key], 1u);
+    else counts[s] = 0;                              // never encoded: contributes no tokens
+  }
+  __syncthreads();
+  if (t < kBinKeys) scan[t] = hist[t];
+  __syncthreads();
+  for (int step = 1; step < kBinKeys; step <<= 1) {  // inclusive scan, all threads reach the barriers
+    uint32_t v = 0;
+    if (t < kBinKeys && t >= step) v = scan[t - step];
     __syncthreads();
-    tmp[t] += v;
+    if (t < kBinKeys) scan[t] += v;
     __syncthreads();
   }
-  c->key_base[t + 1] = tmp[t];
-  if (t == 0) c->key_base[0] = 0;
-  __syncthreads();
-  if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : tmp[(t <= n_tiers ? t : n_tiers) * kLenBuckets - 1];
-}
-
-__global__ void bin_scatter_kernel(const int64_t* offsets, int batch, TierPlan plan, Control* c,
-                                   int32_t* list) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= batch) return;
-  const int64_t len = offsets[s + 1] - offsets[s];
-  const int key = (len < 0 || len > 0x7FFFFFFF) ? -1 : bin_key((int)len, plan);
-  if (key < 0) return;
-  const uint32_t pos = c->key_base[key] + atomicAdd(&c->cursor[key], 1u);
-  list[pos] = s;
+  if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : scan[(t <= plan.n_tiers ? t : plan.n_tiers) * kLenBuckets - 1];
+  if (t < kMaxTiers) c->queue_head[t] = 0;
+  for (int s = t; s < batch; s += 1024) {
+    const int64_t len = offsets[s + 1] - offsets[s];
+    const int key = (len < 0 || len > 0x7FFFFFFF) ? -1 : bin_key((int)len, plan);
+    if (key < 0) continue;
+    const uint32_t pos = (scan[key] - hist[key]) + atomicAdd(&cursor[key], 1u);
+    list[pos] = s;
+  }
 }
 
 // out_offsets[i] = sum of counts[0..i), out_offsets[batch] = total.  One workgroup walks the batch.

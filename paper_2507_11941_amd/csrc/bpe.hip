@@ -311,12 +311,8 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   plan.n_tiers = n_tiers_for(max_len);
   for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_tier_cap[t];
 
-  hipLaunchKernelGGL(zero_control_kernel, dim3(1), dim3(256), 0, stream, ctrl);
   if (batch > 0) {
-    const int blocks = (batch + 255) / 256;
-    hipLaunchKernelGGL(bin_count_kernel, dim3(blocks), dim3(256), 0, stream, offsets, batch, plan, ctrl, counts);
-    hipLaunchKernelGGL(bin_scan_kernel, dim3(1), dim3(kBinKeys), 0, stream, ctrl, plan.n_tiers);
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3(blocks), dim3(256), 0, stream, offsets, batch, plan, ctrl, list);
+    hipLaunchKernelGGL(bin_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, plan, ctrl, list, counts);
 
     EncodeParams p;
     p.table.buckets = (const uint4*)table->d_mem;
@@ -392,9 +388,7 @@ int bpe_read_profile(float* total_ms, int32_t* calls) {
 }
 
 #ifdef BPE_TRACE
-int bpe_debug_dump(unsigned int* out) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_dbg), sizeof(unsigned int) * 64 * 16) == hipSuccess ? BPE_OK : BPE_EHIP;
-}
+// Debug build only: copy out (and optionally clear) the per-phase clock sums of encode_kernel.h.
 int bpe_debug_trace(unsigned long long* out, int reset) {
   if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_trace), sizeof(unsigned long long) * 32) != hipSuccess) return BPE_EHIP;
   if (reset) {

@@ -278,9 +278,10 @@ constexpr int kChunk = 16;
 constexpr int kGroup = 4;
 constexpr int kProbes = 4;     // table probes a lane keeps in flight
 
+// Optional per-phase timing (compile with -DBPE_TRACE): thread 0 of workgroup 0 accumulates the shader
+// clock spent in each phase of encode_string into g_trace; bpe_debug_trace() reads it back.
 #ifdef BPE_TRACE
 __device__ unsigned long long g_trace[32];
-__device__ unsigned int g_dbg[64 * 16];
 #define TRACE_T(var) const unsigned long long var = (blockIdx.x == 0) ? __builtin_readcyclecounter() : 0ull
 #define TRACE_ADD(slot, t0, t1) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[slot] += (t1) - (t0); } while (0)
 #else
@@ -499,14 +500,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     // my first token is consumed if the pair ending at it is applied by the lane before me
     const bool skip_first = live != 0 && in_val < ev && !(firstv < in_val) && pin == 0;
     const bool touched = skip_first || applied != 0;
-#ifdef BPE_TRACE
-    if (blockIdx.x == 0 && pass == 0 && tid < 64) {
-      unsigned int* q = g_dbg + tid * 16;
-      q[0] = (unsigned)live; q[1] = (unsigned)cm; q[2] = elem; q[3] = pin; q[4] = in_val; q[5] = nxt_val;
-      q[6] = (unsigned)e0; q[7] = (unsigned)lr; q[8] = (unsigned)nbr; q[9] = (unsigned)applied; q[10] = skip_first;
-      q[11] = firstv; q[12] = lastv; q[13] = ev; q[14] = llim; q[15] = (unsigned)d;
-    }
-#endif
     mask_t dirty = 0;                                  // positions whose pair must be looked up again
     if (__ballot(touched)) {
       for (mask_t m = applied; m; m &= m - 1) {

@@ -1,0 +1,65 @@
+"""Per-phase time breakdown of the encode kernel (developer tool).
+
+    python -m paper_2507_11941_amd.trace_phases [config] [batch]
+
+Builds a second copy of the library with -DBPE_TRACE (libbpe_hip_trace.so), encodes `batch` strings of the
+configuration once and prints, for the first string that workgroup 0 encodes, the shader-clock ticks thread 0
+spent in each phase of the pass loop, plus the pass count.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import sys
+
+import numpy as np
+
+PHASES = ["load", "horizon+exchange", "sweep", "walk1", "parity scan", "walk2", "successor exchange", "probes",
+          "refresh+publish", "emit", "passes", "total"]
+
+
+def main() -> int:
+    cfg = int(sys.argv[1]) if len(sys.argv) > 1 else 2
+    batch = int(sys.argv[2]) if len(sys.argv) > 2 else 1
+    import torch
+
+    from . import _binding, build as hip_build
+
+    lib_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbpe_hip_trace.so")
+    saved = hip_build.LIB
+    hip_build.LIB = lib_path
+    try:
+        hip_build.build(force=True, extra_flags=("-DBPE_TRACE",))
+    finally:
+        hip_build.LIB = saved
+    _binding._LIB_PATH = lib_path
+    lib = _binding.load_library()
+    lib.bpe_debug_trace.argtypes = [ctypes.c_void_p, ctypes.c_int]
+
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import workloads
+
+    c = workloads.CONFIGS[cfg]
+    table = _binding.build_table(workloads.load_merges(c.table))
+    data, off = workloads.batch(cfg, batch_override=batch)
+    dev = torch.device("cuda:0")
+    d, o = torch.from_numpy(data).to(dev), torch.from_numpy(off).to(dev)
+    max_len = int(np.diff(off).max())
+    for _ in range(3):
+        _binding.encode_batch(table, d, o, max_len)
+    torch.cuda.synchronize()
+    lib.bpe_debug_trace(None, 1)
+    _binding.encode_batch(table, d, o, max_len)
+    torch.cuda.synchronize()
+    t = np.zeros(32, dtype=np.uint64)
+    lib.bpe_debug_trace(t.ctypes.data, 0)
+    passes = max(int(t[10]), 1)
+    print(f"config {cfg}, batch {batch}: {int(t[10])} passes, {int(t[11])} ticks in all")
+    for name, v in zip(PHASES[:10], t[:10]):
+        per = f"{int(v) / passes:9.0f} / pass" if name not in ("load", "emit") else ""
+        print(f"  {name:20s} {int(v):10d} ticks {100.0 * int(v) / max(int(t[11]), 1):5.1f} %  {per}")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
