@@ -29,7 +29,7 @@ def main() -> int:
     saved = hip_build.LIB
     hip_build.LIB = lib_path
     try:
-        hip_build.build(force=True, extra_flags=("-DBPE_TRACE",))
+        hip_build.build(force=False, extra_flags=("-DBPE_TRACE",))   # only if missing or older than the sources
     finally:
         hip_build.LIB = saved
     _binding._LIB_PATH = lib_path
