@@ -12,6 +12,7 @@
 #include "../../include/bpe.h"
 #include "batch_kernels.h"
 #include "encode_kernel.h"
+#include "encode_segmented.h"
 #include "table_format.h"
 
 using namespace bpe;
@@ -40,13 +41,13 @@ struct Variant {
   int max_grid = 0;               // resident workgroups on the whole device (filled on first use)
 };
 
-template <int NW, int D, bool ST, bool LIM>
+template <int NW, int D, bool ST, bool LIM, bool SEG>
 void launch_variant(const EncodeParams& p, int grid, hipStream_t stream) {
   constexpr size_t lds = encode_lds_bytes<NW, D, ST, LIM>();
-  encode_kernel<NW, D, ST, LIM><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
+  encode_kernel<NW, D, ST, LIM, SEG><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
 }
 
-template <int NW, int D, bool ST, bool LIM>
+template <int NW, int D, bool ST, bool LIM, bool SEG>
 Variant make_variant() {
   Variant v;
   v.waves = NW;
@@ -55,18 +56,18 @@ Variant make_variant() {
   v.limits = LIM;
   v.capacity = 64 * NW * D;
   v.lds = encode_lds_bytes<NW, D, ST, LIM>();
-  v.fn = (const void*)&encode_kernel<NW, D, ST, LIM>;
-  v.launch = &launch_variant<NW, D, ST, LIM>;
+  v.fn = (const void*)&encode_kernel<NW, D, ST, LIM, SEG>;
+  v.launch = &launch_variant<NW, D, ST, LIM, SEG>;
   return v;
 }
 
 // Default plan: <= 1 KiB one wave, <= 4 KiB four waves, <= 16 KiB sixteen waves (all LDS-resident),
 // <= 64 KiB sixteen waves with the per-position arrays staged in HBM.
 Variant g_variants[kMaxTiers] = {
-    make_variant<1, 16, false, true>(),
-    make_variant<4, 16, false, true>(),
-    make_variant<16, 16, false, false>(),   // three arrays of 16 Ki words would not fit the 160 KB of LDS
-    make_variant<16, 64, true, true>(),
+    make_variant<1, 16, false, true, true>(),
+    make_variant<4, 16, false, true, true>(),
+    make_variant<16, 16, false, false, true>(),   // three arrays of 16 Ki words would not fit the 160 KB of LDS
+    make_variant<16, 64, true, true, false>(),    // whole-string horizon; arrays in HBM
 };
 int g_tier_cap[kMaxTiers] = {0, 0, 0, 0};   // string-length bound of each tier (<= the variant's capacity)
 std::once_flag g_variants_once;
@@ -199,6 +200,24 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
     if (fr < 0) fr = r;
   }
 
+  // Byte bigrams that can lie at the junction of a merge: (last byte of the left operand, first byte of the
+  // right operand) of some row.  Between two bytes whose bigram is not among them no merge can ever happen.
+  std::vector<uint8_t> first_byte, last_byte, junction;
+  try {
+    first_byte.resize((size_t)n_merges + 256);
+    last_byte.resize((size_t)n_merges + 256);
+    junction.assign(65536, 0);
+  } catch (const std::bad_alloc&) {
+    return BPE_ENOMEM;
+  }
+  for (int b = 0; b < 256; ++b) first_byte[(size_t)b] = last_byte[(size_t)b] = (uint8_t)b;
+  for (int32_t r = 0; r < n_merges; ++r) {
+    const size_t a = (size_t)merges[2 * r], b = (size_t)merges[2 * r + 1];
+    junction[(size_t)last_byte[a] << 8 | first_byte[b]] = 1;
+    first_byte[256 + (size_t)r] = first_byte[a];
+    last_byte[256 + (size_t)r] = last_byte[b];
+  }
+
   int log2_buckets = kMinLog2Buckets;
   while ((int64_t)kSlotsPerBucket * ((int64_t)1 << log2_buckets) * 2 < (int64_t)n_merges * 5) ++log2_buckets;
   size_t n_words = 0;
@@ -249,6 +268,8 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
     }
     if (fits) break;
   }
+  for (size_t i = 0; i < 65536; ++i)                           // byte pairs that are no row: cut or plain miss
+    if (host[n_words + 256 + i] == 0xFFFFFFFFu && !junction[i]) host[n_words + 256 + i] = kCut;
   uint32_t* byte_word = host.data() + n_words;
   for (uint32_t b = 0; b < 256; ++b)
     byte_word[b] = b | (first_left[b] >= 0 ? kTokCanLeft : 0u) | (first_right[b] >= 0 ? kTokCanRight : 0u);

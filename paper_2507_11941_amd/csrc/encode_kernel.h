@@ -350,6 +350,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
 #pragma unroll
       for (int j = 0; j < kChunk; ++j) {
         const int k = k0 + j;
+        if (v[j] == kCut) v[j] = kNoRank;              // this variant does not use the segment cuts
         if (k < dpad) {                                // positions from c0 on are dead from the start
           const uint32_t lim = v[j] != kNoRank ? limit_of(v[j]) : kNoRank;
           V[k * W + tid] = v[j];
@@ -628,60 +629,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
   TRACE_T(t_end);
   TRACE_ADD(9, t_passes, t_end);
   TRACE_ADD(11, t_start, t_end);
-}
-
-// Persistent workgroups: each claims the next string of its tier until the tier's list is exhausted.
-template <int NW, int D, bool STAGED, bool LIMITS>
-__global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
-  constexpr int W = NW * 64;
-  extern __shared__ uint32_t smem[];
-  uint32_t* cur = smem;
-  uint32_t *T, *V, *L;
-  if (STAGED) {
-    T = p.staged + (size_t)blockIdx.x * ((LIMITS ? 3u : 2u) * W * D);
-    V = T + W * D;
-    L = V + W * D;
-  } else {
-    T = cur; cur += W * D;
-    V = cur; cur += W * D;
-    L = cur;
-    if (LIMITS) cur += W * D;
-  }
-  BlockShared<NW> sh;
-  sh.rec = (WaveRecord*)cur; cur += 2 * NW * (sizeof(WaveRecord) / sizeof(uint32_t));
-  sh.first_tok = cur; cur += 2 * NW;
-  sh.part = cur; cur += 2 * NW;
-  sh.item = cur; cur += 4;
-  uint32_t* byte_word = cur;
-  sh.byte_word = byte_word;
-  for (int i = (int)threadIdx.x; i < 256; i += W) byte_word[i] = p.table.byte_word[i];
-  __syncthreads();
-
-  const uint32_t first = p.tier_base[p.tier], end = p.tier_base[p.tier + 1];
-  for (;;) {
-    // Claim the next item.  Every lane of the first wave takes part in the atomic (lane 0 adds 1, the
-    // others 0) so that no lane-dependent branch sits at the loop boundary: a branch on "thread 0" here,
-    // next to a single-lane store that ends the previous string, lets the compiler send the other lanes
-    // round the loop on their own, past the lane-0 broadcast below.
-    uint32_t claimed = 0;
-    if (NW == 1) {
-      claimed = first + atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
-    } else {
-      if (threadIdx.x < 64) claimed = first + atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
-      if (threadIdx.x == 0) *sh.item = claimed;
-      __syncthreads();
-      claimed = *sh.item;
-      __syncthreads();
-    }
-    const uint32_t item = uniform(claimed);            // lane 0's value, as a scalar
-    if (item >= end) break;
-    encode_string<NW, D, STAGED, LIMITS>(p, (int)uniform((uint32_t)p.list[item]), T, V, L, sh);
-  }
-}
-
-template <int NW, int D, bool STAGED, bool LIMITS>
-constexpr size_t encode_lds_bytes() {
-  return sizeof(uint32_t) * ((STAGED ? 0 : (LIMITS ? 3 : 2) * NW * 64 * D) + 12 * NW + 4 + 256);
 }
 
 }  // namespace bpe

@@ -1,0 +1,484 @@
+// Segment-local horizons: the encoder used for strings whose per-position state fits LDS.
+//
+// Same pass structure as encode_string() in encode_kernel.h (candidates below a horizon, run-parity scan,
+// merge in place, look up the changed pairs), with one difference that cuts the number of passes by another
+// order of magnitude: the horizon is taken per SEGMENT of the string instead of over the whole string.
+//
+// A merge joins a token that ends at byte i with a token that starts at byte i+1, so the bigram
+// (byte i, byte i+1) then lies inside a vocabulary token.  The table builder marks every byte bigram that
+// occurs at no row's junction (last byte of the left operand, first byte of the right operand); between two
+// such bytes no merge can ever happen, whatever the rest of the string holds.  These "cuts" split a string
+// into segments that Algorithm 1 processes without any interaction, so each segment may use its own horizon
+// E = min limit() over its own pairs.  With word-like text a segment is a word, its merges take 5-10
+// fused passes, and all segments of the string advance in the same passes.  Nothing here is a heuristic: a
+// table without such bigrams simply yields one segment per string and the whole-string horizon.
+//
+// Per pass a lane (a) sweeps its limits and values: running minima forward and backward inside its segments
+// give every position its segment minimum, except for the segment that enters the lane from the left and
+// the one that leaves it to the right; (b) those two are completed by a forward and a backward segmented
+// min-scan over the lanes (DPP; between waves through the LDS records); (c) compares each value with its
+// segment's horizon to get the candidate mask.  The rest of the pass is the same as in encode_string().
+#pragma once
+#include "encode_kernel.h"
+
+namespace bpe {
+
+constexpr uint32_t kInf31 = 0x7FFFFFFFu;    // "no pair" in the 31-bit domain of the horizons
+constexpr uint32_t kAll31 = 0x7FFFFFFEu;    // horizon above every rank
+constexpr uint32_t kReset31 = 0x80000000u;  // scan element flag: a cut lies inside this span
+
+// Horizons are kept in a "half-value" domain so that bit 31 is free for the scan flag and a pair value can
+// be compared with a horizon directly: half(limit) = limit << 11, and a pair is a candidate iff
+// (value >> 1) < half(limit), i.e. rank < limit.
+__device__ inline uint32_t half_limit_of(uint32_t value) {
+  if (value == kNoRank) return kInf31;
+  const uint32_t lim = limit_of(value);
+  return lim >= 0xFFFFFu ? kAll31 : (lim << (kRankShift - 1));
+}
+
+// Segmented minimum: apply(left, right) = right if a cut lies inside right, else the minimum of the two with
+// left's flag.  Bit 31 is the flag, bits 0..30 the value; kInf31 (flag clear) is the identity.
+struct OpSegMin {
+  __device__ static uint32_t apply(uint32_t left, uint32_t right) {
+    const uint32_t m = min(left & kInf31, right & kInf31) | (left & kReset31);
+    return (right & kReset31) ? right : m;
+  }
+};
+
+// What a wave tells the others at the start of each pass.
+struct SegRecord {
+  uint32_t fwd;        // segmented-min element of the whole wave, left to right (tail minima)
+  uint32_t bwd;        // the same right to left (head minima)
+  uint32_t first_val;  // pair value at the wave's first live token
+  uint32_t last_val;   // pair value at the wave's last live token
+  uint32_t first_tok;  // first live token word, kTokNone if the wave is empty
+  uint32_t any_pair;   // 1 if any pair of the wave is in the table
+  uint32_t pad0, pad1;
+};
+
+template <int NW, int D, bool LIMITS>
+__device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* __restrict__ T,
+                                        uint32_t* __restrict__ V, uint32_t* __restrict__ L,
+                                        const BlockShared<NW>& sh) {
+  static_assert(D % kGroup == 0 && D <= 16, "the per-position registers of the sweep are sized for 16");
+  using mask_t = uint32_t;
+  constexpr int W = NW * 64;
+  const int tid = (int)threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const DeviceTable& tab = p.table;
+  SegRecord* const rec_base = (SegRecord*)sh.rec;
+
+  const int64_t begin = p.offsets[s];
+  const int n = (int)uniform((uint32_t)(p.offsets[s + 1] - begin));
+  if (n <= 0) {                                        // uniform branch
+    if (tid == W - 1) p.counts[s] = 0;
+    return;
+  }
+  TRACE_T(t_start);
+  const uint8_t* src = p.bytes + begin;
+  const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D (uniform)
+  int c0 = n - tid * d;                                // my byte count
+  c0 = c0 < 0 ? 0 : (c0 > d ? d : c0);
+
+  mask_t live = bits_below<mask_t>(c0);                // c0 <= 16
+  mask_t cuts = 0;                                     // positions that start a segment (they never die)
+  uint32_t ftok = kTokNone;                            // my first live token word
+  uint32_t succ_tok = kTokNone;                        // the token my last pair is looked up against
+  uint32_t firstv = kNoRank, lastv = kNoRank;          // pair values at my first / last live position
+
+  // ---- load: byte-level pre-tokenisation (section 4.1), id = byte value; the initial pair values, one
+  //      lookup per adjacent byte pair in the direct 256 x 256 table; and the cuts ----
+  {
+    const int base = tid * d;
+    uint32_t b[D + 2];                                 // b[j] = byte (base - 1 + j) of the string, 0x100 = none
+#pragma unroll
+    for (int j = 0; j < D + 2; ++j) {
+      const int i = base - 1 + j;
+      b[j] = (j <= c0 + 1 && c0 > 0 && i >= 0 && i < n) ? src[i] : 0x100u;
+    }
+    uint32_t raw[D + 1];                               // raw[j]: table entry of the pair (b[j], b[j+1])
+#pragma unroll
+    for (int j = 0; j < D + 1; ++j)
+      raw[j] = (j <= c0 && b[j] < 0x100u && b[j + 1] < 0x100u) ? tab.byte_pair[(b[j] << 8) | b[j + 1]] : kCut;
+    // raw[0] is the pair that ends at my first byte; the start of the string counts as a cut
+    if (c0 > 0 && raw[0] == kCut) cuts |= 1u;
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      if (k < d) {                                     // positions from c0 on are dead from the start
+        uint32_t v = k < c0 ? raw[k + 1] : kNoRank;
+        if (v == kCut) {
+          v = kNoRank;
+          if (k + 1 < c0) cuts |= bit_at<mask_t>(k + 1);
+        }
+        V[k * W + tid] = v;
+        if (LIMITS) L[k * W + tid] = half_limit_of(v);
+        if (k < c0) {
+          const uint32_t w = sh.byte_word[b[k + 1]];
+          T[k * W + tid] = w;
+          if (k == 0) { ftok = w; firstv = v; }
+          if (k == c0 - 1) {
+            lastv = v;
+            if (b[k + 2] < 0x100u) succ_tok = sh.byte_word[b[k + 2]];
+          }
+        }
+      }
+    }
+  }
+  const int first_cut = cuts ? ctz_bits<mask_t>(cuts) : 32;
+  const int last_cut = cuts ? top_bit<mask_t>(cuts) : 32;   // 32: none, every position belongs to the head
+  TRACE_T(t_loaded);
+  TRACE_ADD(0, t_start, t_loaded);
+
+  // ---- merge passes ----
+  // Every pass removes at least one token, so n passes can never be needed; the bound only guarantees
+  // that the loop ends whatever the memory contents.
+  int buf = 0;                                         // which half of the double-buffered exchange is current
+  for (int pass = 0; pass < n; ++pass) {
+    TRACE_T(t0);
+    // -- sweep: values and limits of my positions; minima inside my segments --
+    uint32_t v[D], e[D], f[D];                         // e[k]: limit of k, later the horizon of k's segment
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      if (k < d) {
+        v[k] = V[k * W + tid];
+        if (LIMITS) e[k] = L[k * W + tid];
+      }
+    }
+    uint32_t run = kInf31;                             // forward: minimum since my last cut so far
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      if (k < d) {
+        if (!LIMITS) e[k] = half_limit_of(v[k]);
+        run = (cuts >> k & 1u) ? e[k] : min(run, e[k]);
+        f[k] = run;
+      }
+    }
+    const uint32_t tail_min = run;                     // over my positions from my last cut on (all, if none)
+    run = kInf31;                                      // backward: minimum up to the end of the segment
+#pragma unroll
+    for (int k = D - 1; k >= 0; --k) {
+      if (k < d) {
+        run = min(run, e[k]);
+        e[k] = min(f[k], run);                         // minimum of the part of k's segment that is mine
+        if (cuts >> k & 1u) run = kInf31;
+      }
+    }
+    const uint32_t head_min = run;                     // over my positions before my first cut (all, if none)
+    TRACE_T(t1);
+    TRACE_ADD(1, t0, t1);
+
+    // -- complete the segments that cross lanes: forward and backward segmented min-scans --
+    const uint32_t flag = cuts ? kReset31 : 0u;
+    const uint32_t fwd_inc = wave_scan<OpSegMin>(flag | tail_min, kInf31);
+    uint32_t in_fwd = wave_shift_up(fwd_inc, kInf31);
+    const uint32_t rev = lane_read(flag | head_min, 63 - lane);
+    const uint32_t bwd_inc_rev = wave_scan<OpSegMin>(rev, kInf31);
+    const uint32_t bwd_exc_rev = wave_shift_up(bwd_inc_rev, kInf31);
+    uint32_t in_bwd = lane_read(bwd_exc_rev, 63 - lane);
+
+    // -- values just outside my column: the pair ending at my first token, the pair after my last --
+    const uint64_t ne = __ballot(live != 0);
+    const uint64_t below = ne & ((1ull << lane) - 1ull);
+    const uint64_t above = lane == 63 ? 0ull : (ne >> (lane + 1)) << (lane + 1);
+    uint32_t in_val = lane_read(lastv, below ? 63 - __builtin_clzll(below) : lane);
+    uint32_t nxt_val = lane_read(firstv, above ? __builtin_ctzll(above) : lane);
+    if (!below) in_val = kNoRank;
+    if (!above) nxt_val = kNoRank;
+
+    bool any_pair;
+    if (NW == 1) {
+      any_pair = true;                                 // decided below from the candidate masks
+    } else {
+      // any pair in my wave: some position has a finite limit
+      uint32_t mine = kInf31;
+#pragma unroll
+      for (int k = 0; k < D; ++k)
+        if (k < d) mine = min(mine, e[k]);
+      const uint64_t havep = __ballot(mine != kInf31);
+      const int fl = ne ? __builtin_ctzll(ne) : 0, ll = ne ? 63 - __builtin_clzll(ne) : 0;
+      const uint32_t fv = lane_read(firstv, fl), ft = lane_read(ftok, fl), lv = lane_read(lastv, ll);
+      const uint32_t fwd_total = (uint32_t)__builtin_amdgcn_readlane((int)fwd_inc, 63);
+      const uint32_t bwd_total = (uint32_t)__builtin_amdgcn_readlane((int)bwd_inc_rev, 63);
+      if (lane == 0) {
+        SegRecord r;
+        r.fwd = fwd_total;
+        r.bwd = bwd_total;
+        r.first_val = ne ? fv : kNoRank;
+        r.last_val = ne ? lv : kNoRank;
+        r.first_tok = ne ? ft : kTokNone;
+        r.any_pair = havep ? 1u : 0u;
+        r.pad0 = r.pad1 = 0;
+        rec_base[buf * NW + wave] = r;
+      }
+      __syncthreads();                                 // records of all waves are in place
+      const SegRecord* rec = rec_base + buf * NW;
+      uint32_t anyp = 0, pre = kInf31, suf = kInf31;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) anyp |= rec[w].any_pair;
+      for (int w = 0; w < wave; ++w) pre = OpSegMin::apply(pre, rec[w].fwd);          // left to right
+      for (int w = NW - 1; w > wave; --w) suf = OpSegMin::apply(suf, rec[w].bwd);      // right to left
+      in_fwd = OpSegMin::apply(pre, in_fwd);
+      in_bwd = OpSegMin::apply(suf, in_bwd);
+      any_pair = uniform(anyp) != 0;
+      if (!below) {
+        for (int w = wave - 1; w >= 0; --w)            // nearest earlier non-empty wave
+          if (rec[w].first_tok != kTokNone) { in_val = rec[w].last_val; break; }
+      }
+      if (!above) {
+        for (int w = wave + 1; w < NW; ++w)            // nearest later non-empty wave
+          if (rec[w].first_tok != kTokNone) { nxt_val = rec[w].first_val; break; }
+      }
+    }
+    if (NW > 1 && !any_pair) break;                    // uniform: every wave read the same records
+
+    // horizons of the segment that enters my column and of the one that leaves it
+    const bool through = cuts == 0;
+    const uint32_t e_head = min(min(in_fwd & kInf31, head_min), through ? (in_bwd & kInf31) : kInf31);
+    const uint32_t e_tail = min(min(in_bwd & kInf31, tail_min), through ? (in_fwd & kInf31) : kInf31);
+
+    // -- candidates: pairs whose rank is below their segment's horizon --
+    mask_t cm = 0;
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      if (k < d) {
+        uint32_t ek = e[k];
+        ek = k < first_cut ? e_head : ek;
+        ek = (k >= last_cut && last_cut < 32) ? e_tail : ek;
+        cm |= (mask_t)((v[k] >> 1) < ek ? 1u : 0u) << k;
+      }
+    }
+    if (NW == 1 && !__ballot(cm != 0)) break;          // a segment with pairs always has a candidate
+    TRACE_T(t2);
+    TRACE_ADD(2, t1, t2);
+
+    // -- walk 1 over my candidates: which are beaten by a neighbour, and my element of the parity scan --
+    // (see encode_string(); a candidate and the neighbour that beats it are always in the same segment,
+    //  because the pair across a cut is not in the table)
+    mask_t e0 = 0, lr = 0, nbr = 0;
+    uint32_t elem = live ? 2u : 0u;                    // no trailing run: my last pair restarts the count
+    if (__ballot(cm != 0)) {
+      int prevc = -1;
+      uint32_t prevv = 0, prev_dl = 0;
+      bool prev_lead = false, prev_bl = false;
+      for (mask_t m = cm; m; m &= m - 1) {
+        const int k = ctz_bits<mask_t>(m);
+        const uint32_t vk = V[k * W + tid];
+        const mask_t lower = live & bits_below<mask_t>(k);
+        bool bl, lead;
+        uint32_t dl;
+        if (lower) {
+          const bool adjacent = top_bit<mask_t>(lower) == prevc;   // the live position before k is a candidate
+          bl = adjacent && prevv <= vk;
+          if (prevc >= 0 && !(adjacent && vk < prevv)) nbr |= bit_at<mask_t>(prevc);
+          dl = bl ? (prev_dl ^ 1u) : 0u;
+          lead = bl && prev_lead;
+        } else {                                       // k is my first live position
+          bl = in_val <= vk;                           // same segment and lower rank: a candidate too
+          dl = bl ? 1u : 0u;
+          lead = bl;
+        }
+        if (dl == 0) e0 |= bit_at<mask_t>(k);
+        if (lead) lr |= bit_at<mask_t>(k);
+        prevc = k;
+        prevv = vk;
+        prev_dl = dl;
+        prev_lead = lead;
+        prev_bl = bl;
+      }
+      if (prevc >= 0) {
+        const bool is_last = (live & bits_above<mask_t>(prevc)) == 0;
+        if (!(is_last && nxt_val < prevv)) nbr |= bit_at<mask_t>(prevc);
+        if (is_last && prev_bl) elem = (prev_lead ? 0u : 2u) | prev_dl;
+      }
+    }
+    TRACE_T(t3);
+    TRACE_ADD(3, t2, t3);
+    // parity of the run of left-beaten candidates that ends at the last live token before my column
+    uint32_t pin;
+    {
+      const uint32_t inc = wave_scan<OpParity>(elem, 0u);
+      uint32_t exc = wave_shift_up(inc, 0u);
+      if (NW > 1) {
+        const uint32_t wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+        if (lane == 0) sh.part[buf * NW + wave] = wave_total;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w) before = OpParity::apply(before, sh.part[buf * NW + w]);
+        exc = OpParity::apply(before, exc);
+      }
+      pin = exc & 1u;
+    }
+    TRACE_T(t4);
+    TRACE_ADD(4, t3, t4);
+
+    // -- walk 2 over the candidates that are applied: merge --
+    const mask_t applied = cm & nbr & (pin ? (e0 ^ lr) : e0);
+    // my first token is consumed if the pair ending at it is a candidate applied by the lane before me;
+    // that pair belongs to the segment that enters my column
+    const bool skip_first = live != 0 && (in_val >> 1) < e_head && !(firstv < in_val) && pin == 0 && !(cuts & 1u);
+    const bool touched = skip_first || applied != 0;
+    mask_t dirty = 0;                                  // positions whose pair must be looked up again
+    if (__ballot(touched)) {
+      for (mask_t m = applied; m; m &= m - 1) {
+        const int k = ctz_bits<mask_t>(m);
+        T[k * W + tid] = merged_token_word(V[k * W + tid]);
+        const mask_t upper = live & bits_above<mask_t>(k);
+        if (upper) {                                   // the right operand is mine: it dies
+          const int kn = ctz_bits<mask_t>(upper);
+          live &= ~bit_at<mask_t>(kn);
+          V[kn * W + tid] = kNoRank;
+          if (LIMITS) L[kn * W + tid] = kInf31;
+        }                                              // else it is the next lane's first token (skip_first there)
+        dirty |= bit_at<mask_t>(k);
+        const mask_t lower = live & bits_below<mask_t>(k);
+        if (lower) dirty |= bit_at<mask_t>(top_bit<mask_t>(lower));
+      }
+      if (skip_first) {
+        const int fk = ctz_bits<mask_t>(live);
+        live &= ~bit_at<mask_t>(fk);
+        V[fk * W + tid] = kNoRank;
+        if (LIMITS) L[fk * W + tid] = kInf31;
+      }
+      dirty &= live;
+      if (touched) ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
+    }
+    TRACE_T(t5);
+    TRACE_ADD(5, t4, t5);
+
+    // -- who follows me now, and did the token there change? --
+    {
+      const uint64_t ne2 = __ballot(live != 0);
+      uint32_t next_wave_tok = kTokNone;
+      if (NW > 1) {
+        const uint32_t first = lane_read(ftok, ne2 ? __builtin_ctzll(ne2) : 0);
+        if (lane == 0) sh.first_tok[buf * NW + wave] = ne2 ? first : kTokNone;
+        __syncthreads();
+        for (int w = wave + 1; w < NW; ++w) {
+          const uint32_t t = sh.first_tok[buf * NW + w];
+          if (t != kTokNone) { next_wave_tok = t; break; }
+        }
+      }
+      const uint64_t above2 = lane == 63 ? 0ull : (ne2 >> (lane + 1)) << (lane + 1);
+      uint32_t st = lane_read(ftok, above2 ? __builtin_ctzll(above2) : lane);
+      if (!above2) st = next_wave_tok;
+      if (live != 0 && st != succ_tok) {
+        succ_tok = st;
+        dirty |= bit_at<mask_t>(top_bit<mask_t>(live));
+      }
+    }
+    TRACE_T(t6);
+    TRACE_ADD(6, t5, t6);
+
+    // -- look up the pairs that changed, kProbes at a time --
+    const bool refresh = touched || dirty != 0;
+    while (__ballot(dirty != 0)) {
+      int k[kProbes];
+      uint32_t x[kProbes], y[kProbes];
+      ProbeInFlight pf[kProbes];
+#pragma unroll
+      for (int j = 0; j < kProbes; ++j) {
+        k[j] = -1;
+        x[j] = 0;
+        y[j] = kTokNone;
+        if (dirty) {
+          k[j] = ctz_bits<mask_t>(dirty);
+          dirty &= dirty - 1;
+          x[j] = T[k[j] * W + tid];
+          const mask_t upper = live & bits_above<mask_t>(k[j]);
+          y[j] = upper ? T[ctz_bits<mask_t>(upper) * W + tid] : succ_tok;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kProbes; ++j) probe_start(tab, x[j], y[j], k[j] >= 0, pf[j]);
+#pragma unroll
+      for (int j = 0; j < kProbes; ++j) {
+        if (k[j] >= 0) {
+          const uint32_t nv = probe_finish(tab, pf[j]);
+          V[k[j] * W + tid] = nv;
+          if (LIMITS) L[k[j] * W + tid] = half_limit_of(nv);
+        }
+      }
+    }
+    if (refresh) {
+      firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
+      lastv = live ? V[top_bit<mask_t>(live) * W + tid] : kNoRank;
+    }
+    buf ^= 1;
+    TRACE_T(t7);
+    TRACE_ADD(7, t6, t7);
+    TRACE_ADD(10, 0ull, 1ull);
+  }
+  TRACE_T(t_passes);
+
+  // ---- emit: prefix sum of live counts gives each lane's write index (section 4.3's compaction) ----
+  uint32_t total;
+  const uint32_t out0 = block_prefix_sum<NW>((uint32_t)pop_bits<mask_t>(live), sh, lane, wave, &total);
+  int32_t* dst = p.tmp_ids + begin + out0;
+  for (mask_t m = live; m; m &= m - 1) *dst++ = (int32_t)(T[ctz_bits<mask_t>(m) * W + tid] & kTokIdMask);
+  if (tid == W - 1) p.counts[s] = (int32_t)total;
+  block_sync<NW>();                                    // the LDS exchange arrays are reused by the next string
+  TRACE_T(t_end);
+  TRACE_ADD(9, t_passes, t_end);
+  TRACE_ADD(11, t_start, t_end);
+}
+
+// Persistent workgroups: each claims the next string of its tier until the tier's list is exhausted.
+// SEGMENTED selects encode_string_segmented() (LDS variants with at most 16 positions per lane).
+template <int NW, int D, bool STAGED, bool LIMITS, bool SEGMENTED>
+__global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
+  static_assert(!(SEGMENTED && STAGED), "the segmented encoder keeps its arrays in LDS");
+  constexpr int W = NW * 64;
+  extern __shared__ uint32_t smem[];
+  uint32_t* cur = smem;
+  uint32_t *T, *V, *L;
+  if (STAGED) {
+    T = p.staged + (size_t)blockIdx.x * ((LIMITS ? 3u : 2u) * W * D);
+    V = T + W * D;
+    L = V + W * D;
+  } else {
+    T = cur; cur += W * D;
+    V = cur; cur += W * D;
+    L = cur;
+    if (LIMITS) cur += W * D;
+  }
+  BlockShared<NW> sh;
+  sh.rec = (WaveRecord*)cur; cur += 2 * NW * 8;        // room for either record type
+  sh.first_tok = cur; cur += 2 * NW;
+  sh.part = cur; cur += 2 * NW;
+  sh.item = cur; cur += 4;
+  uint32_t* byte_word = cur;
+  sh.byte_word = byte_word;
+  for (int i = (int)threadIdx.x; i < 256; i += W) byte_word[i] = p.table.byte_word[i];
+  __syncthreads();
+
+  const uint32_t first = p.tier_base[p.tier], end = p.tier_base[p.tier + 1];
+  for (;;) {
+    // Claim the next item.  Every lane of the first wave takes part in the atomic (lane 0 adds 1, the
+    // others 0) so that no lane-dependent branch sits at the loop boundary: a branch on "thread 0" here,
+    // next to a single-lane store that ends the previous string, lets the compiler send the other lanes
+    // round the loop on their own, past the lane-0 broadcast below.
+    uint32_t claimed = 0;
+    if (NW == 1) {
+      claimed = first + atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
+    } else {
+      if (threadIdx.x < 64) claimed = first + atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
+      if (threadIdx.x == 0) *sh.item = claimed;
+      __syncthreads();
+      claimed = *sh.item;
+      __syncthreads();
+    }
+    const uint32_t item = uniform(claimed);            // lane 0's value, as a scalar
+    if (item >= end) break;
+    const int s = (int)uniform((uint32_t)p.list[item]);
+    if constexpr (SEGMENTED) encode_string_segmented<NW, D, LIMITS>(p, s, T, V, L, sh);
+    else encode_string<NW, D, STAGED, LIMITS>(p, s, T, V, L, sh);
+  }
+}
+
+template <int NW, int D, bool STAGED, bool LIMITS>
+constexpr size_t encode_lds_bytes() {
+  return sizeof(uint32_t) * ((STAGED ? 0 : (LIMITS ? 3 : 2) * NW * 64 * D) + 20 * NW + 4 + 256);
+}
+
+}  // namespace bpe

@@ -43,7 +43,7 @@
 namespace bpe {
 
 constexpr uint32_t kNoRank = 0xFFFFFFFFu;     // "pair not in table"; larger than any value
-constexpr uint32_t kDirty = 0xFFFFFFFEu;      // "pair changed, look it up again" (kernel-internal marker)
+constexpr uint32_t kCut = 0xFFFFFFFDu;        // byte-pair table only: not a pair, and no token spans this bigram
 constexpr uint32_t kNoLimit = 0xFFFFFFFEu;    // limit of a row whose token is never an operand
 constexpr uint32_t kFlagLeft = 2u;
 constexpr uint32_t kFlagRight = 4u;
