@@ -348,6 +348,9 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     p.queue_head = ctrl->queue_head;
     p.tmp_ids = tmp_ids;
     p.counts = counts;
+    // Warming L2 pays once the batch probes the table more often than it has lines: ~1 probe per input byte.
+    const size_t table_bytes = table->bucket_bytes + (256 + 65536) * sizeof(uint32_t);
+    p.prefetch_lines = (size_t)total_bytes >= table_bytes / 4 ? (uint32_t)(table_bytes / 128) : 0u;
 
     int prof_slot = -1;
     if (g_profiling) {

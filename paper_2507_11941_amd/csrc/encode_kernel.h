@@ -57,6 +57,7 @@ struct EncodeParams {
   int32_t* tmp_ids;           // ids of string s are written at tmp_ids[offsets[s] ...]
   int32_t* counts;            // [batch] token count of each string
   uint32_t* staged;           // HBM staging for the variant whose strings exceed LDS (else null)
+  uint32_t prefetch_lines;    // 128-byte lines of table memory to pull into L2 at kernel start (0 = none)
   int tier;
 };
 

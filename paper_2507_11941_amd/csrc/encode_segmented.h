@@ -450,29 +450,50 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   uint32_t* byte_word = cur;
   sh.byte_word = byte_word;
   for (int i = (int)threadIdx.x; i < 256; i += W) byte_word[i] = p.table.byte_word[i];
+
+  // Warm this XCD's L2 with the merge table.  L2 contents do not survive a kernel boundary, so without this
+  // every first probe of a bucket pays a trip to the Infinity Cache in the middle of a merge pass; here the
+  // same lines come in as one bandwidth-bound stream while the first strings are still being loaded.
+  // Workgroups are dealt to the 8 XCDs round robin, so workgroups b, b+8, b+16, ... share an L2 and split
+  // the table between them.  (Only a hint: a different placement just makes it less effective.)
+  if (p.prefetch_lines > 0) {
+    constexpr uint32_t kXcds = 8;
+    const uint32_t peers = (gridDim.x + kXcds - 1) / kXcds;            // workgroups that share my L2
+    const uint32_t me = blockIdx.x / kXcds;
+    const uint32_t per = (p.prefetch_lines + peers - 1) / peers;        // 128-byte lines for each of them
+    const uint32_t lo = me * per, hi = min(lo + per, p.prefetch_lines);
+    uint32_t sink = 0;
+    for (uint32_t line = lo + threadIdx.x; line < hi; line += W)
+      sink |= __builtin_nontemporal_load((const uint32_t*)p.table.buckets + (size_t)line * 32);
+    if (sink == 0x9E3779B9u && p.prefetch_lines == 0xFFFFFFFFu) byte_word[0] = sink;   // keeps the loads alive
+  }
   __syncthreads();
 
+  // Work items: the first one is my workgroup index, later ones come from the tier's atomic counter (which
+  // starts at zero and is offset by the grid size).  When the grid covers the whole list no atomic is needed.
   const uint32_t first = p.tier_base[p.tier], end = p.tier_base[p.tier + 1];
-  for (;;) {
+  const uint32_t count = end - first;
+  uint32_t item = blockIdx.x;
+  while (item < count) {
+    const int s = (int)uniform((uint32_t)p.list[first + item]);
+    if constexpr (SEGMENTED) encode_string_segmented<NW, D, LIMITS>(p, s, T, V, L, sh);
+    else encode_string<NW, D, STAGED, LIMITS>(p, s, T, V, L, sh);
+    if (gridDim.x >= count) break;                     // uniform: one item per workgroup at most
     // Claim the next item.  Every lane of the first wave takes part in the atomic (lane 0 adds 1, the
     // others 0) so that no lane-dependent branch sits at the loop boundary: a branch on "thread 0" here,
     // next to a single-lane store that ends the previous string, lets the compiler send the other lanes
     // round the loop on their own, past the lane-0 broadcast below.
     uint32_t claimed = 0;
     if (NW == 1) {
-      claimed = first + atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
+      claimed = atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
     } else {
-      if (threadIdx.x < 64) claimed = first + atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
+      if (threadIdx.x < 64) claimed = atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
       if (threadIdx.x == 0) *sh.item = claimed;
       __syncthreads();
       claimed = *sh.item;
       __syncthreads();
     }
-    const uint32_t item = uniform(claimed);            // lane 0's value, as a scalar
-    if (item >= end) break;
-    const int s = (int)uniform((uint32_t)p.list[item]);
-    if constexpr (SEGMENTED) encode_string_segmented<NW, D, LIMITS>(p, s, T, V, L, sh);
-    else encode_string<NW, D, STAGED, LIMITS>(p, s, T, V, L, sh);
+    item = gridDim.x + uniform(claimed);               // lane 0's value, as a scalar
   }
 }
 
