@@ -73,9 +73,9 @@ size_t bpe_workspace_bytes(int32_t batch, int64_t total_bytes, int32_t max_len);
  *   batch        number of strings, >= 0.
  *   total_bytes  offsets[batch], passed by the host so that the call needs no device-to-host read.
  *   max_len      an upper bound on the longest string, <= BPE_MAX_STRING_BYTES, passed by the host for the
- *                same reason.  It selects which kernel variants are launched.  Pass the true maximum: a
- *                string too long for the variants that max_len selects is not encoded and contributes zero
- *                tokens (no out-of-bounds access happens).
+ *                same reason.  It selects which kernel variants are launched.  Pass the true maximum: for a
+ *                string longer than max_len the output is unspecified (it may be encoded, or contribute
+ *                zero tokens); the other strings are unaffected and no out-of-bounds access happens.
  *   out_ids      DEVICE, int32, capacity >= total_bytes ids (a string never has more tokens than bytes).
  *   out_offsets  DEVICE, int64[batch+1].
  *   workspace    DEVICE, >= bpe_workspace_bytes(batch, total_bytes, max_len) bytes, 256-byte aligned,

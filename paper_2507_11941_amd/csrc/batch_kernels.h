@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "table_format.h"
+
 namespace bpe {
 
 constexpr int kMaxTiers = 4;
@@ -21,6 +23,11 @@ struct TierPlan {
 struct Control {
   uint32_t tier_base[kMaxTiers + 1];                 // start of each tier's slice of the list
   uint32_t queue_head[kMaxTiers];                    // work-queue heads of the encode kernels
+  // used only when strings are split into pieces:
+  uint32_t n_slots;                                  // piece slots in the batch
+  uint32_t hist[kBinKeys];                           // pieces per (tier, length bucket)
+  uint32_t key_base[kBinKeys];                       // exclusive scan of hist
+  uint32_t cursor[kBinKeys];                         // scatter cursors
 };
 
 __device__ inline int bin_key(int len, const TierPlan& plan) {
@@ -107,6 +114,243 @@ __global__ __launch_bounds__(256) void pack_kernel(const int32_t* tmp_ids, const
   for (int s = blockIdx.x; s < batch; s += gridDim.x) {
     const int64_t src = offsets[s], dst = out_offsets[s];
     const int k = (int)(out_offsets[s + 1] - dst);
+    for (int i = threadIdx.x; i < k; i += blockDim.x) out_ids[dst + i] = tmp_ids[src + i];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Splitting long strings into pieces.
+//
+// No merge can cross a cut (a byte bigram that occurs at no merge junction, see table_format.h), so the two
+// sides of a cut are encoded independently and their ids concatenated.  Strings longer than the piece target
+// P are therefore cut near every multiple of P: the string gets ceil(len / P) "slots"; slot 0 starts at the
+// string's first byte, slot i at the last cut within kCutWindow bytes before byte i*P, or is void if there is
+// none (then the piece before it simply runs on).  Pieces, not strings, are what the encode kernels work on;
+// their ids land in tmp_ids at the piece's own byte offset, so a string's ids are the concatenation of its
+// slots' runs.
+
+constexpr int kCutWindow = 128;
+
+// One workgroup: slots per string, their exclusive scan (slot_base), and the owner string of every slot.
+__global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offsets, int batch, int piece_target,
+                                                           int max_string, Control* c, int32_t* slot_base,
+                                                           int32_t* slot_string) {
+  __shared__ uint32_t wave_sum[16];
+  __shared__ uint32_t carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  if (tid < kBinKeys) { c->hist[tid] = 0; c->cursor[tid] = 0; }
+  if (tid < kMaxTiers) c->queue_head[tid] = 0;
+  __syncthreads();
+  for (int base = 0; base < batch; base += 1024) {
+    const int s = base + tid;
+    uint32_t m = 0;
+    if (s < batch) {
+      const int64_t len = offsets[s + 1] - offsets[s];
+      m = (len <= 0 || len > max_string) ? 1u : (uint32_t)((len + piece_target - 1) / piece_target);
+    }
+    uint32_t v = m;
+    for (int step = 1; step < 64; step <<= 1) {
+      const uint32_t o = (uint32_t)__shfl_up((int)v, step, 64);
+      if (lane >= step) v += o;
+    }
+    if (lane == 63) wave_sum[wave] = v;
+    __syncthreads();
+    uint32_t before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    const uint32_t first = before + v - m;
+    if (s < batch) {
+      slot_base[s] = (int32_t)first;
+      for (uint32_t i = 0; i < m; ++i) slot_string[first + i] = s;
+    }
+    __syncthreads();
+    if (tid == 1023) carry_s = before + v;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    slot_base[batch] = (int32_t)carry_s;
+    c->n_slots = carry_s;
+  }
+}
+
+// One wave per slot: where does its piece start?
+__global__ __launch_bounds__(256) void cut_search_kernel(const uint8_t* bytes, const int64_t* offsets,
+                                                         const uint32_t* byte_pair, int piece_target,
+                                                         int max_string, const Control* c, const int32_t* slot_base,
+                                                         const int32_t* slot_string, int64_t* piece_begin) {
+  const uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (g >= c->n_slots) return;
+  const int s = slot_string[g];
+  const int i = (int)g - slot_base[s];
+  const int64_t begin = offsets[s];
+  const int64_t len = offsets[s + 1] - begin;
+  int64_t start = -1;                                  // void unless a cut is found
+  if (len < 0 || len > max_string) {
+    start = -1;                                        // not encodable: the string yields no tokens
+  } else if (i == 0) {
+    start = begin;
+  } else {
+    // candidates q = t, t-1, ..., t-127 (a cut "before q" lies between bytes q-1 and q); lane l checks
+    // t-2l and t-2l-1.  piece_target >= 2 * kCutWindow keeps q-2 inside the string.
+    const int64_t t = begin + (int64_t)i * piece_target;
+    const int64_t q0 = t - 2 * lane;
+    const uint32_t a = bytes[q0 - 2], b = bytes[q0 - 1], cc = bytes[q0];
+    const bool cut0 = byte_pair[(b << 8) | cc] == kCut;      // before q0
+    const bool cut1 = byte_pair[(a << 8) | b] == kCut;       // before q0 - 1
+    const uint64_t m0 = __ballot(cut0), m1 = __ballot(cut1);
+    const uint64_t any = m0 | m1;
+    if (any) {
+      const int l = __builtin_ctzll(any);                    // the lane with the largest candidates
+      start = (m0 >> l & 1) ? t - 2 * l : t - 2 * l - 1;
+    }
+  }
+  if (lane == 0) piece_begin[g] = start;
+}
+
+// One thread per slot: piece lengths, and the histogram of (tier, length bucket) keys.
+__global__ __launch_bounds__(256) void piece_hist_kernel(const int64_t* offsets, TierPlan plan, Control* c,
+                                                         const int32_t* slot_base, const int32_t* slot_string,
+                                                         const int64_t* piece_begin, int32_t* piece_len,
+                                                         int32_t* counts) {
+  __shared__ uint32_t hist[kBinKeys];
+  hist[threadIdx.x] = 0;                               // 256 threads, 256 keys
+  __syncthreads();
+  const uint32_t n_slots = c->n_slots;
+  for (uint32_t g = blockIdx.x * 256 + threadIdx.x; g < n_slots; g += gridDim.x * 256) {
+    const int64_t start = piece_begin[g];
+    int32_t len = 0;
+    int key = -1;
+    if (start >= 0) {
+      const int s = slot_string[g];
+      int64_t next = offsets[s + 1];
+      for (int h = (int)g + 1; h < slot_base[s + 1]; ++h)
+        if (piece_begin[h] >= 0) { next = piece_begin[h]; break; }
+      len = (int32_t)(next - start);
+      key = bin_key(len, plan);
+      if (key >= 0) atomicAdd(&hist[key], 1u);
+    }
+    piece_len[g] = len;
+    if (key < 0) counts[g] = 0;                        // void slot, or too long for the launched variants
+  }
+  __syncthreads();
+  if (hist[threadIdx.x]) atomicAdd(&c->hist[threadIdx.x], hist[threadIdx.x]);
+}
+
+// One workgroup of 256: exclusive scan of the key histogram, list bases of the tiers.
+__global__ __launch_bounds__(256) void piece_scan_kernel(Control* c, int n_tiers) {
+  __shared__ uint32_t scan[kBinKeys];
+  const int t = threadIdx.x;
+  const uint32_t mine = c->hist[t];
+  scan[t] = mine;
+  __syncthreads();
+  for (int step = 1; step < kBinKeys; step <<= 1) {
+    const uint32_t v = t >= step ? scan[t - step] : 0;
+    __syncthreads();
+    scan[t] += v;
+    __syncthreads();
+  }
+  c->key_base[t] = scan[t] - mine;
+  if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : scan[(t <= n_tiers ? t : n_tiers) * kLenBuckets - 1];
+}
+
+// One thread per slot: scatter the pieces into the work list, tier-major, longest bucket first.
+__global__ __launch_bounds__(256) void piece_scatter_kernel(TierPlan plan, Control* c, const int64_t* piece_begin,
+                                                            const int32_t* piece_len, int32_t* list) {
+  const uint32_t n_slots = c->n_slots;
+  for (uint32_t g = blockIdx.x * 256 + threadIdx.x; g < n_slots; g += gridDim.x * 256) {
+    if (piece_begin[g] < 0) continue;
+    const int key = bin_key(piece_len[g], plan);
+    if (key < 0) continue;
+    list[c->key_base[key] + atomicAdd(&c->cursor[key], 1u)] = (int32_t)g;
+  }
+}
+
+// Token offsets of the slots: per-tile sums, scan of the tile sums, then the scan inside each tile.
+constexpr int kScanTile = 4096;
+
+__global__ __launch_bounds__(1024) void tile_sum_kernel(const int32_t* counts, const Control* c, int64_t* tile_sum) {
+  __shared__ int64_t wave_sum[16];
+  const uint32_t n_slots = c->n_slots;
+  const uint32_t base = blockIdx.x * kScanTile;
+  int64_t v = 0;
+  for (int j = 0; j < kScanTile / 1024; ++j) {
+    const uint32_t g = base + j * 1024 + threadIdx.x;
+    if (g < n_slots) v += counts[g];
+  }
+  for (int step = 32; step >= 1; step >>= 1) v += __shfl_down(v, step, 64);
+  if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int64_t t = 0;
+    for (int w = 0; w < 16; ++w) t += wave_sum[w];
+    tile_sum[blockIdx.x] = t;
+  }
+}
+
+__global__ __launch_bounds__(64) void tile_scan_kernel(int64_t* tile_sum, int n_tiles, const Control* c,
+                                                       int64_t* out_offsets, int batch) {
+  // one wave walks the tiles (there are few: one per 4096 slots); tile_sum becomes the exclusive scan
+  const int lane = threadIdx.x;
+  const int used = (int)((c->n_slots + kScanTile - 1) / kScanTile);
+  int64_t carry = 0;
+  for (int base = 0; base < n_tiles; base += 64) {
+    const int i = base + lane;
+    const int64_t m = (i < n_tiles && i < used) ? tile_sum[i] : 0;
+    int64_t v = m;
+    for (int step = 1; step < 64; step <<= 1) {
+      const int64_t o = __shfl_up(v, step, 64);
+      if (lane >= step) v += o;
+    }
+    if (i < n_tiles) tile_sum[i] = carry + v - m;
+    carry += __shfl(v, 63, 64);
+  }
+  if (lane == 0) out_offsets[batch] = carry;
+}
+
+__global__ __launch_bounds__(1024) void slot_offsets_kernel(const int32_t* counts, const Control* c,
+                                                            const int64_t* tile_base, const int32_t* slot_base,
+                                                            const int32_t* slot_string, int64_t* slot_out,
+                                                            int64_t* out_offsets) {
+  __shared__ int64_t wave_sum[16];
+  __shared__ int64_t carry_s;
+  const uint32_t n_slots = c->n_slots;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) carry_s = tile_base[blockIdx.x];
+  __syncthreads();
+  for (int j = 0; j < kScanTile / 1024; ++j) {
+    const uint32_t g = blockIdx.x * kScanTile + j * 1024 + tid;
+    const int64_t m = g < n_slots ? (int64_t)counts[g] : 0;
+    int64_t v = m;
+    for (int step = 1; step < 64; step <<= 1) {
+      const int64_t o = __shfl_up(v, step, 64);
+      if (lane >= step) v += o;
+    }
+    if (lane == 63) wave_sum[wave] = v;
+    __syncthreads();
+    int64_t before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    if (g < n_slots) {
+      const int64_t at = before + v - m;
+      slot_out[g] = at;
+      const int s = slot_string[g];
+      if ((uint32_t)slot_base[s] == g) out_offsets[s] = at;   // a string starts at its first slot
+    }
+    __syncthreads();
+    if (tid == 1023) carry_s = before + v;
+    __syncthreads();
+  }
+}
+
+// One workgroup per slot: copy the piece's ids to their place in the dense output.
+__global__ __launch_bounds__(256) void piece_pack_kernel(const int32_t* tmp_ids, const Control* c,
+                                                         const int64_t* piece_begin, const int32_t* counts,
+                                                         const int64_t* slot_out, int32_t* out_ids) {
+  const uint32_t n_slots = c->n_slots;
+  for (uint32_t g = blockIdx.x; g < n_slots; g += gridDim.x) {
+    const int k = counts[g];
+    if (k <= 0) continue;
+    const int64_t src = piece_begin[g], dst = slot_out[g];
     for (int i = threadIdx.x; i < k; i += blockDim.x) out_ids[dst + i] = tmp_ids[src + i];
   }
 }

@@ -2,6 +2,7 @@
 // batch encode.  Everything numeric happens in the kernels of encode_kernel.h / batch_kernels.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -135,17 +136,38 @@ size_t staged_slab_bytes(const Variant& v) {
 
 constexpr size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Strings longer than this are cut into pieces at segment cuts (see batch_kernels.h).  A piece starts at most
+// kCutWindow - 1 bytes before a multiple of the target, so pieces stay within the one-wave variant's 1 KiB.
+constexpr int kPieceTarget = 1024 - kCutWindow;
+
 struct WorkspaceLayout {
-  size_t control, list, counts, tmp_ids, staged, total;
+  bool split;                        // strings are cut into pieces
+  int64_t max_slots;                 // upper bound on the number of work items (strings or piece slots)
+  int n_tiles;                       // scan tiles over the slots
+  size_t control, list, counts, tmp_ids, staged;
+  size_t slot_base, slot_string, piece_begin, piece_len, slot_out, tile_sum;   // split only
+  size_t total;
 };
 
 WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) {
   WorkspaceLayout w;
+  w.split = max_len > g_variants[0].capacity;   // everything already fits the one-wave variant otherwise
+  w.max_slots = w.split ? (int64_t)batch + total_bytes / kPieceTarget : (int64_t)batch;
+  w.n_tiles = (int)((w.max_slots + kScanTile - 1) / kScanTile);
   size_t at = 0;
   w.control = at; at += align_up(sizeof(Control));
-  w.list = at; at += align_up((size_t)batch * sizeof(int32_t));
-  w.counts = at; at += align_up((size_t)batch * sizeof(int32_t));
+  w.list = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
+  w.counts = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.tmp_ids = at; at += align_up((size_t)total_bytes * sizeof(int32_t));
+  w.slot_base = w.slot_string = w.piece_begin = w.piece_len = w.slot_out = w.tile_sum = 0;
+  if (w.split) {
+    w.slot_base = at; at += align_up(((size_t)batch + 1) * sizeof(int32_t));
+    w.slot_string = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
+    w.piece_begin = at; at += align_up((size_t)w.max_slots * sizeof(int64_t));
+    w.piece_len = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
+    w.slot_out = at; at += align_up((size_t)w.max_slots * sizeof(int64_t));
+    w.tile_sum = at; at += align_up((size_t)(w.n_tiles + 1) * sizeof(int64_t));
+  }
   w.staged = at;
   const int nt = n_tiers_for(max_len);
   for (int t = 0; t < nt; ++t)
@@ -332,8 +354,35 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   plan.n_tiers = n_tiers_for(max_len);
   for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_tier_cap[t];
 
+  const int64_t* piece_begin = nullptr;
+  const int32_t* piece_len = nullptr;
+  const int32_t* slot_base = nullptr;
+  const int32_t* slot_string = nullptr;
+  const int n_items_max = (int)w.max_slots;              // grid bound for the encode kernels
   if (batch > 0) {
-    hipLaunchKernelGGL(bin_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, plan, ctrl, list, counts);
+    if (!w.split) {
+      hipLaunchKernelGGL(bin_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, plan, ctrl, list, counts);
+    } else {
+      int32_t* sb = (int32_t*)(ws + w.slot_base);
+      int32_t* ss = (int32_t*)(ws + w.slot_string);
+      int64_t* pb = (int64_t*)(ws + w.piece_begin);
+      int32_t* pl = (int32_t*)(ws + w.piece_len);
+      const uint32_t* byte_pair =
+          (const uint32_t*)((const char*)table->d_mem + table->bucket_bytes) + 256;
+      const int per_slot_grid = (int)std::min<int64_t>((w.max_slots + 255) / 256, 65536);
+      hipLaunchKernelGGL(slot_layout_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, kPieceTarget,
+                         BPE_MAX_STRING_BYTES, ctrl, sb, ss);
+      hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 3) / 4)), dim3(256), 0, stream, bytes,
+                         offsets, byte_pair, kPieceTarget, BPE_MAX_STRING_BYTES, ctrl, sb, ss, pb);
+      hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
+                         pb, pl, counts);
+      hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
+      hipLaunchKernelGGL(piece_scatter_kernel, dim3(per_slot_grid), dim3(256), 0, stream, plan, ctrl, pb, pl, list);
+      piece_begin = pb;
+      piece_len = pl;
+      slot_base = sb;
+      slot_string = ss;
+    }
 
     EncodeParams p;
     p.table.buckets = (const uint4*)table->d_mem;
@@ -343,6 +392,8 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     p.table.bucket_mask = ((uint32_t)1 << table->log2_buckets) - 1;
     p.bytes = bytes;
     p.offsets = offsets;
+    p.piece_begin = piece_begin;
+    p.piece_len = piece_len;
     p.list = list;
     p.tier_base = ctrl->tier_base;
     p.queue_head = ctrl->queue_head;
@@ -369,7 +420,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     size_t staged_at = w.staged;
     for (int t = 0; t < plan.n_tiers; ++t) {
       const Variant& v = g_variants[t];
-      int grid = v.max_grid < batch ? v.max_grid : batch;
+      int grid = v.max_grid < n_items_max ? v.max_grid : n_items_max;
       p.tier = t;
       p.staged = nullptr;
       if (v.staged) {
@@ -381,10 +432,22 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     }
     if (prof_slot >= 0 && hipEventRecord(g_prof.end[prof_slot], stream) != hipSuccess) return BPE_EHIP;
   }
-  hipLaunchKernelGGL(offsets_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, batch, out_offsets);
-  if (batch > 0) {
-    const int grid = batch < 65536 ? batch : 65536;
-    hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, offsets, out_offsets, batch, out_ids);
+  if (!w.split) {
+    hipLaunchKernelGGL(offsets_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, batch, out_offsets);
+    if (batch > 0) {
+      const int grid = batch < 65536 ? batch : 65536;
+      hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, offsets, out_offsets, batch, out_ids);
+    }
+  } else {
+    int64_t* tile_sum = (int64_t*)(ws + w.tile_sum);
+    int64_t* slot_out = (int64_t*)(ws + w.slot_out);
+    hipLaunchKernelGGL(tile_sum_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum);
+    hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(64), 0, stream, tile_sum, w.n_tiles, ctrl, out_offsets, batch);
+    hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
+                       slot_string, slot_out, out_offsets);
+    const int grid = (int)std::min<int64_t>(w.max_slots, 262144);
+    hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
+                       slot_out, out_ids);
   }
   return hipGetLastError() == hipSuccess ? BPE_OK : BPE_EHIP;
 }

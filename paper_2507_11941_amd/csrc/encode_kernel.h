@@ -51,11 +51,13 @@ struct EncodeParams {
   DeviceTable table;
   const uint8_t* bytes;
   const int64_t* offsets;
-  const int32_t* list;        // string indices of all tiers, tier-major, longest first inside a tier
+  const int64_t* piece_begin; // when strings are split: first byte of each piece (absolute), else null
+  const int32_t* piece_len;   //                         and its length
+  const int32_t* list;        // work items (strings or pieces) of all tiers, tier-major, longest first inside a tier
   const uint32_t* tier_base;  // [tiers+1] start of each tier's slice of `list`
   uint32_t* queue_head;       // [tiers] next unclaimed item of each tier
-  int32_t* tmp_ids;           // ids of string s are written at tmp_ids[offsets[s] ...]
-  int32_t* counts;            // [batch] token count of each string
+  int32_t* tmp_ids;           // ids of an item are written at tmp_ids[first byte of the item ...]
+  int32_t* counts;            // token count of each item
   uint32_t* staged;           // HBM staging for the variant whose strings exceed LDS (else null)
   uint32_t prefetch_lines;    // 128-byte lines of table memory to pull into L2 at kernel start (0 = none)
   int tier;
@@ -314,8 +316,9 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
   const int wave = tid >> 6;
   const DeviceTable& tab = p.table;
 
-  const int64_t begin = p.offsets[s];
-  const int n = (int)uniform((uint32_t)(p.offsets[s + 1] - begin));
+  // a work item is a whole string, or a piece of one between two cuts
+  const int64_t begin = p.piece_begin ? p.piece_begin[s] : p.offsets[s];
+  const int n = (int)uniform((uint32_t)(p.piece_len ? p.piece_len[s] : (int32_t)(p.offsets[s + 1] - begin)));
   if (n <= 0) {                                        // uniform branch
     if (tid == W - 1) p.counts[s] = 0;
     return;

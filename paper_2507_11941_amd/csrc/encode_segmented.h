@@ -69,8 +69,9 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
   const DeviceTable& tab = p.table;
   SegRecord* const rec_base = (SegRecord*)sh.rec;
 
-  const int64_t begin = p.offsets[s];
-  const int n = (int)uniform((uint32_t)(p.offsets[s + 1] - begin));
+  // a work item is a whole string, or a piece of one between two cuts
+  const int64_t begin = p.piece_begin ? p.piece_begin[s] : p.offsets[s];
+  const int n = (int)uniform((uint32_t)(p.piece_len ? p.piece_len[s] : (int32_t)(p.offsets[s + 1] - begin)));
   if (n <= 0) {                                        // uniform branch
     if (tid == W - 1) p.counts[s] = 0;
     return;
