@@ -254,16 +254,27 @@ __global__ __launch_bounds__(256) void piece_scan_kernel(Control* c, int n_tiers
   if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : scan[(t <= n_tiers ? t : n_tiers) * kLenBuckets - 1];
 }
 
-// One thread per slot: scatter the pieces into the work list, tier-major, longest bucket first.
+// One thread per slot: scatter the pieces into the work list, tier-major, longest bucket first.  Pieces of a
+// long text all have about the same length, hence the same key: a workgroup first ranks its pieces per key in
+// LDS and then reserves each key's range of the list with one global atomic.
 __global__ __launch_bounds__(256) void piece_scatter_kernel(TierPlan plan, Control* c, const int64_t* piece_begin,
                                                             const int32_t* piece_len, int32_t* list) {
-  const uint32_t n_slots = c->n_slots;
-  for (uint32_t g = blockIdx.x * 256 + threadIdx.x; g < n_slots; g += gridDim.x * 256) {
-    if (piece_begin[g] < 0) continue;
-    const int key = bin_key(piece_len[g], plan);
-    if (key < 0) continue;
-    list[c->key_base[key] + atomicAdd(&c->cursor[key], 1u)] = (int32_t)g;
+  __shared__ uint32_t local[kBinKeys];                 // 256 threads, 256 keys
+  local[threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t g = blockIdx.x * 256 + threadIdx.x;
+  int key = -1;
+  uint32_t rank = 0;
+  if (g < c->n_slots && piece_begin[g] >= 0) {
+    key = bin_key(piece_len[g], plan);
+    if (key >= 0) rank = atomicAdd(&local[key], 1u);
   }
+  __syncthreads();
+  const uint32_t mine = local[threadIdx.x];
+  __syncthreads();
+  if (mine) local[threadIdx.x] = c->key_base[threadIdx.x] + atomicAdd(&c->cursor[threadIdx.x], mine);
+  __syncthreads();
+  if (key >= 0) list[local[key] + rank] = (int32_t)g;
 }
 
 // Token offsets of the slots: per-tile sums, scan of the tile sums, then the scan inside each tile.

@@ -377,7 +377,8 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
       hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
                          pb, pl, counts);
       hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
-      hipLaunchKernelGGL(piece_scatter_kernel, dim3(per_slot_grid), dim3(256), 0, stream, plan, ctrl, pb, pl, list);
+      hipLaunchKernelGGL(piece_scatter_kernel, dim3((unsigned)((w.max_slots + 255) / 256)), dim3(256), 0, stream, plan,
+                         ctrl, pb, pl, list);
       piece_begin = pb;
       piece_len = pl;
       slot_base = sb;
