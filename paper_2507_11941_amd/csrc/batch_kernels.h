@@ -108,6 +108,28 @@ __global__ __launch_bounds__(1024) void offsets_scan_kernel(const int32_t* count
   }
 }
 
+// Small batches: offsets and packing in one launch.  Workgroup s sums the counts before its string itself
+// (the batch is at most a few thousand strings), writes out_offsets[s] and copies the string's ids.
+__global__ __launch_bounds__(256) void scan_pack_kernel(const int32_t* tmp_ids, const int64_t* offsets,
+                                                        const int32_t* counts, int batch, int64_t* out_offsets,
+                                                        int32_t* out_ids) {
+  __shared__ int64_t wave_sum[4];
+  const int s = blockIdx.x;
+  int64_t v = 0;
+  for (int i = threadIdx.x; i < s; i += 256) v += counts[i];
+  for (int step = 32; step >= 1; step >>= 1) v += __shfl_down(v, step, 64);
+  if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const int64_t dst = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+  const int k = counts[s];
+  if (threadIdx.x == 0) {
+    out_offsets[s] = dst;
+    if (s == batch - 1) out_offsets[batch] = dst + k;
+  }
+  const int64_t src = offsets[s];
+  for (int i = threadIdx.x; i < k; i += 256) out_ids[dst + i] = tmp_ids[src + i];
+}
+
 // One workgroup per string: copy its ids from the per-string staging area to the dense output.
 __global__ __launch_bounds__(256) void pack_kernel(const int32_t* tmp_ids, const int64_t* offsets,
                                                    const int64_t* out_offsets, int batch, int32_t* out_ids) {

@@ -359,8 +359,12 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   const int32_t* slot_base = nullptr;
   const int32_t* slot_string = nullptr;
   const int n_items_max = (int)w.max_slots;              // grid bound for the encode kernels
+  // A batch that one variant's resident grid covers needs no work list: workgroup i encodes string i.
+  const bool direct = !w.split && plan.n_tiers == 1 && batch <= g_variants[0].max_grid;
   if (batch > 0) {
-    if (!w.split) {
+    if (direct) {
+      list = nullptr;
+    } else if (!w.split) {
       hipLaunchKernelGGL(bin_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, plan, ctrl, list, counts);
     } else {
       int32_t* sb = (int32_t*)(ws + w.slot_base);
@@ -400,6 +404,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     p.queue_head = ctrl->queue_head;
     p.tmp_ids = tmp_ids;
     p.counts = counts;
+    p.direct_count = (uint32_t)batch;
     // Warming L2 pays once the batch probes the table more often than it has lines: ~1 probe per input byte.
     const size_t table_bytes = table->bucket_bytes + (256 + 65536) * sizeof(uint32_t);
     p.prefetch_lines = (size_t)total_bytes >= table_bytes / 4 ? (uint32_t)(table_bytes / 128) : 0u;
@@ -433,7 +438,10 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     }
     if (prof_slot >= 0 && hipEventRecord(g_prof.end[prof_slot], stream) != hipSuccess) return BPE_EHIP;
   }
-  if (!w.split) {
+  if (!w.split && batch > 0 && batch <= 4096) {
+    hipLaunchKernelGGL(scan_pack_kernel, dim3(batch), dim3(256), 0, stream, tmp_ids, offsets, counts, batch,
+                       out_offsets, out_ids);
+  } else if (!w.split) {
     hipLaunchKernelGGL(offsets_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, batch, out_offsets);
     if (batch > 0) {
       const int grid = batch < 65536 ? batch : 65536;

@@ -60,6 +60,7 @@ struct EncodeParams {
   int32_t* counts;            // token count of each item
   uint32_t* staged;           // HBM staging for the variant whose strings exceed LDS (else null)
   uint32_t prefetch_lines;    // 128-byte lines of table memory to pull into L2 at kernel start (0 = none)
+  uint32_t direct_count;      // when `list` is null: items are the strings 0..direct_count-1, one per workgroup
   int tier;
 };
 
@@ -319,7 +320,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
   // a work item is a whole string, or a piece of one between two cuts
   const int64_t begin = p.piece_begin ? p.piece_begin[s] : p.offsets[s];
   const int n = (int)uniform((uint32_t)(p.piece_len ? p.piece_len[s] : (int32_t)(p.offsets[s + 1] - begin)));
-  if (n <= 0) {                                        // uniform branch
+  if (n <= 0 || n > W * D) {                           // uniform branch; too long only if max_len was wrong
     if (tid == W - 1) p.counts[s] = 0;
     return;
   }

@@ -72,7 +72,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
   // a work item is a whole string, or a piece of one between two cuts
   const int64_t begin = p.piece_begin ? p.piece_begin[s] : p.offsets[s];
   const int n = (int)uniform((uint32_t)(p.piece_len ? p.piece_len[s] : (int32_t)(p.offsets[s + 1] - begin)));
-  if (n <= 0) {                                        // uniform branch
+  if (n <= 0 || n > W * D) {                           // uniform branch; too long only if max_len was wrong
     if (tid == W - 1) p.counts[s] = 0;
     return;
   }
@@ -472,11 +472,12 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
 
   // Work items: the first one is my workgroup index, later ones come from the tier's atomic counter (which
   // starts at zero and is offset by the grid size).  When the grid covers the whole list no atomic is needed.
-  const uint32_t first = p.tier_base[p.tier], end = p.tier_base[p.tier + 1];
-  const uint32_t count = end - first;
+  // (With a single variant in use and a grid that covers the batch there is no list at all: item = string.)
+  const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
+  const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
   uint32_t item = blockIdx.x;
   while (item < count) {
-    const int s = (int)uniform((uint32_t)p.list[first + item]);
+    const int s = p.list ? (int)uniform((uint32_t)p.list[first + item]) : (int)item;
     if constexpr (SEGMENTED) encode_string_segmented<NW, D, LIMITS>(p, s, T, V, L, sh);
     else encode_string<NW, D, STAGED, LIMITS>(p, s, T, V, L, sh);
     if (gridDim.x >= count) break;                     // uniform: one item per workgroup at most
