@@ -79,6 +79,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
   TRACE_T(t_start);
   const uint8_t* src = p.bytes + begin;
   const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D (uniform)
+  const int dpad = (d + kGroup - 1) / kGroup * kGroup; // the sweeps work on whole groups: pad with dead positions
   int c0 = n - tid * d;                                // my byte count
   c0 = c0 < 0 ? 0 : (c0 > d ? d : c0);
 
@@ -106,7 +107,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     if (c0 > 0 && raw[0] == kCut) cuts |= 1u;
 #pragma unroll
     for (int k = 0; k < D; ++k) {
-      if (k < d) {                                     // positions from c0 on are dead from the start
+      if (k < dpad) {                                  // positions from c0 on are dead from the start
         uint32_t v = k < c0 ? raw[k + 1] : kNoRank;
         if (v == kCut) {
           v = kNoRank;
@@ -138,34 +139,47 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
   for (int pass = 0; pass < n; ++pass) {
     TRACE_T(t0);
     // -- sweep: values and limits of my positions; minima inside my segments --
+    // Per-position conditions are taken as 0 / all-ones words with bit-field extracts so that the running
+    // minima are three or four vector instructions per position and no lane mask has to stay live.
     uint32_t v[D], e[D], f[D];                         // e[k]: limit of k, later the horizon of k's segment
 #pragma unroll
-    for (int k = 0; k < D; ++k) {
-      if (k < d) {
-        v[k] = V[k * W + tid];
-        if (LIMITS) e[k] = L[k * W + tid];
+    for (int g = 0; g < D; g += kGroup) {
+      if (g < d) {
+#pragma unroll
+        for (int k = g; k < g + kGroup; ++k) {
+          v[k] = V[k * W + tid];
+          if (LIMITS) e[k] = L[k * W + tid];
+        }
       }
     }
     uint32_t run = kInf31;                             // forward: minimum since my last cut so far
 #pragma unroll
-    for (int k = 0; k < D; ++k) {
-      if (k < d) {
-        if (!LIMITS) e[k] = half_limit_of(v[k]);
-        run = (cuts >> k & 1u) ? e[k] : min(run, e[k]);
-        f[k] = run;
+    for (int g = 0; g < D; g += kGroup) {
+      if (g < d) {
+#pragma unroll
+        for (int k = g; k < g + kGroup; ++k) {
+          if (!LIMITS) e[k] = half_limit_of(v[k]);
+          const uint32_t at_cut = (uint32_t)__builtin_amdgcn_sbfe((int)cuts, k, 1);   // all ones at a cut
+          run = min(run | at_cut, e[k]);               // a cut restarts the minimum (limits are < 2^31)
+          f[k] = run;
+        }
       }
     }
-    const uint32_t tail_min = run;                     // over my positions from my last cut on (all, if none)
+    const uint32_t tail_min = run & kInf31;            // over my positions from my last cut on (all, if none)
     run = kInf31;                                      // backward: minimum up to the end of the segment
 #pragma unroll
-    for (int k = D - 1; k >= 0; --k) {
-      if (k < d) {
-        run = min(run, e[k]);
-        e[k] = min(f[k], run);                         // minimum of the part of k's segment that is mine
-        if (cuts >> k & 1u) run = kInf31;
+    for (int g = D - kGroup; g >= 0; g -= kGroup) {
+      if (g < d) {
+#pragma unroll
+        for (int k = g + kGroup - 1; k >= g; --k) {
+          const uint32_t at_cut = (uint32_t)__builtin_amdgcn_sbfe((int)cuts, k, 1);
+          run = min(run, e[k]);
+          e[k] = min(f[k], run);                       // minimum of the part of k's segment that is mine
+          run |= at_cut;                               // the segment starts here: restart for the one before
+        }
       }
     }
-    const uint32_t head_min = run;                     // over my positions before my first cut (all, if none)
+    const uint32_t head_min = min(run, kInf31);        // over my positions before my first cut (all, if none)
     TRACE_T(t1);
     TRACE_ADD(1, t0, t1);
 
@@ -194,8 +208,12 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       // any pair in my wave: some position has a finite limit
       uint32_t mine = kInf31;
 #pragma unroll
-      for (int k = 0; k < D; ++k)
-        if (k < d) mine = min(mine, e[k]);
+      for (int g = 0; g < D; g += kGroup) {
+        if (g < d) {
+#pragma unroll
+          for (int k = g; k < g + kGroup; ++k) mine = min(mine, e[k]);
+        }
+      }
       const uint64_t havep = __ballot(mine != kInf31);
       const int fl = ne ? __builtin_ctzll(ne) : 0, ll = ne ? 63 - __builtin_clzll(ne) : 0;
       const uint32_t fv = lane_read(firstv, fl), ft = lane_read(ftok, fl), lv = lane_read(lastv, ll);
@@ -239,14 +257,23 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     const uint32_t e_tail = min(min(in_bwd & kInf31, tail_min), through ? (in_fwd & kInf31) : kInf31);
 
     // -- candidates: pairs whose rank is below their segment's horizon --
+    // positions before my first cut take the entering segment's horizon, positions from my last cut on the
+    // leaving segment's, the others the minimum found inside my column
+    const mask_t head_pos = first_cut >= 32 ? ~(mask_t)0 : bits_below<mask_t>(first_cut);
+    const mask_t tail_pos = last_cut >= 32 ? (mask_t)0 : ~bits_below<mask_t>(last_cut);
     mask_t cm = 0;
 #pragma unroll
-    for (int k = 0; k < D; ++k) {
-      if (k < d) {
-        uint32_t ek = e[k];
-        ek = k < first_cut ? e_head : ek;
-        ek = (k >= last_cut && last_cut < 32) ? e_tail : ek;
-        cm |= (mask_t)((v[k] >> 1) < ek ? 1u : 0u) << k;
+    for (int g = 0; g < D; g += kGroup) {
+      if (g < d) {
+#pragma unroll
+        for (int k = g; k < g + kGroup; ++k) {
+          const uint32_t in_head = (uint32_t)__builtin_amdgcn_sbfe((int)head_pos, k, 1);
+          const uint32_t in_tail = (uint32_t)__builtin_amdgcn_sbfe((int)tail_pos, k, 1);
+          uint32_t ek = (e_head & in_head) | (e[k] & ~in_head);
+          ek = (e_tail & in_tail) | (ek & ~in_tail);
+          // both sides are below 2^31, so the sign of the difference is the comparison
+          cm |= (((v[k] >> 1) - ek) >> 31) << k;
+        }
       }
     }
     if (NW == 1 && !__ballot(cm != 0)) break;          // a segment with pairs always has a candidate
