@@ -35,7 +35,24 @@ def measured_traffic(config: int):
     return int(m.group(1)) if m else None
 
 
-def cpu_baseline(merges, data, offsets, target_seconds=2.5):
+def stream_copy_gbs(dev, nbytes=1 << 30, reps=5):
+    """Read + written bytes per second of a plain device-to-device copy: the ceiling an HBM-bound kernel could
+    reach on this machine, for comparison with the published peak."""
+    import torch
+
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * reps / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+
+
+def cpu_baseline(merges, data, offsets, target_seconds=1.5):
     """The oracle's textbook sequential encoder on all host threads, on repetitions of the same batch."""
     import oracle
 
@@ -160,6 +177,7 @@ def main() -> int:
                      "kernel_calls_timed": kernel_calls},
     }
     if not args.no_cpu_baseline:
+        result["stream_copy_GBs"] = stream_copy_gbs(dev)
         base, want = cpu_baseline(merges, data, offsets)
         got = out_ids[:n_tokens].cpu().numpy()
         result["cpu_baseline"] = base

@@ -14,7 +14,8 @@ import sys
 
 import numpy as np
 
-PHASES = ["load", "horizon+exchange", "sweep", "walk1", "parity scan", "walk2", "successor exchange", "probes",
+PHASES = ["load", "minima sweep", "scans+neighbours+candidates", "walk1", "parity scan", "walk2",
+          "successor exchange", "probes",
           "refresh+publish", "emit", "passes", "total"]
 
 
@@ -57,7 +58,7 @@ def main() -> int:
     print(f"config {cfg}, batch {batch}: {int(t[10])} passes, {int(t[11])} ticks in all")
     for name, v in zip(PHASES[:10], t[:10]):
         per = f"{int(v) / passes:9.0f} / pass" if name not in ("load", "emit") else ""
-        print(f"  {name:20s} {int(v):10d} ticks {100.0 * int(v) / max(int(t[11]), 1):5.1f} %  {per}")
+        print(f"  {name:28s} {int(v):10d} ticks {100.0 * int(v) / max(int(t[11]), 1):5.1f} %  {per}")
     return 0
 
 
