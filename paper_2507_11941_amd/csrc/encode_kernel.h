@@ -288,9 +288,22 @@ constexpr int kProbes = 2;     // table probes a lane keeps in flight (measured:
 __device__ unsigned long long g_trace[32];
 #define TRACE_T(var) const unsigned long long var = (blockIdx.x == 0) ? __builtin_readcyclecounter() : 0ull
 #define TRACE_ADD(slot, t0, t1) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[slot] += (t1) - (t0); } while (0)
+// one count per trip of a (possibly divergent) loop, and a sum over lanes
+#ifdef BPE_TRACE_COUNTS   // these disturb the clock figures: a build of its own
+// trips of a divergent loop that runs `cnt` times in each lane (the wave runs it max-over-lanes times), and a
+// sum over lanes
+#define TRACE_MAXTRIPS(slot, cnt) do { if (blockIdx.x == 0) { const int c_ = (cnt); int t_ = 0; \
+    while (__ballot(c_ > t_)) ++t_; if (threadIdx.x == 0) g_trace[slot] += t_; } } while (0)
+#define TRACE_LANES(slot, v) do { if (blockIdx.x == 0) atomicAdd(&g_trace[slot], (unsigned long long)(v)); } while (0)
+#else
+#define TRACE_MAXTRIPS(slot, cnt)
+#define TRACE_LANES(slot, v)
+#endif
 #else
 #define TRACE_T(var)
 #define TRACE_ADD(slot, t0, t1)
+#define TRACE_MAXTRIPS(slot, cnt)
+#define TRACE_LANES(slot, v)
 #endif
 
 template <class M> __device__ inline int ctz_bits(M m);

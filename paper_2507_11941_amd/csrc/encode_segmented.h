@@ -127,6 +127,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       }
     }
   }
+  const uint64_t cut_first = __ballot((cuts & 1u) != 0);   // lanes whose column starts a segment (for good)
   const int first_cut = cuts ? ctz_bits<mask_t>(cuts) : 32;
   const int last_cut = cuts ? top_bit<mask_t>(cuts) : 32;   // 32: none, every position belongs to the head
   TRACE_T(t_loaded);
@@ -351,6 +352,8 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       for (mask_t m = applied; m; m &= m - 1) {
         const int k = ctz_bits<mask_t>(m);
         T[k * W + tid] = merged_token_word(V[k * W + tid]);
+        V[k * W + tid] = kNoRank;                      // until the new pair is looked up (if it needs to be)
+        if (LIMITS) L[k * W + tid] = kInf31;
         const mask_t upper = live & bits_above<mask_t>(k);
         if (upper) {                                   // the right operand is mine: it dies
           const int kn = ctz_bits<mask_t>(upper);
@@ -394,12 +397,26 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         succ_tok = st;
         dirty |= bit_at<mask_t>(top_bit<mask_t>(live));
       }
+      // A pair that straddles a cut is in no table, so it needs no look-up (its value is "none" already).
+      // In reversed bit order the live position before each cut is the first live bit above the cut, which
+      // a carry finds for all cuts at once: add the cuts, shifted up, to the dead positions.
+      const uint32_t rl = __builtin_bitreverse32(live), rc = __builtin_bitreverse32(cuts);
+      mask_t cross = __builtin_bitreverse32((~rl + (rc << 1)) & rl);
+      if (above2 && live != 0 && ((cut_first >> __builtin_ctzll(above2)) & 1ull))
+        cross |= bit_at<mask_t>(top_bit<mask_t>(live));                // my last token and the next lane's first
+      dirty &= ~cross;
     }
     TRACE_T(t6);
     TRACE_ADD(6, t5, t6);
 
     // -- look up the pairs that changed, kProbes at a time --
     const bool refresh = touched || dirty != 0;
+    TRACE_MAXTRIPS(12, pop_bits<mask_t>(cm));
+    TRACE_MAXTRIPS(13, pop_bits<mask_t>(applied));
+    TRACE_MAXTRIPS(8, (pop_bits<mask_t>(dirty) + kProbes - 1) / kProbes);
+    TRACE_LANES(14, pop_bits<mask_t>(dirty));
+    TRACE_LANES(15, pop_bits<mask_t>(cm));
+    TRACE_LANES(16, pop_bits<mask_t>(applied));
     while (__ballot(dirty != 0)) {
       int k[kProbes];
       uint32_t x[kProbes], y[kProbes];

@@ -1,6 +1,6 @@
 """Per-phase time breakdown of the encode kernel (developer tool).
 
-    python -m paper_2507_11941_amd.trace_phases [config] [batch]
+    python -m paper_2507_11941_amd.trace_phases [--counts] [config] [batch]
 
 Builds a second copy of the library with -DBPE_TRACE (libbpe_hip_trace.so), encodes `batch` strings of the
 configuration once and prints, for the first string that workgroup 0 encodes, the shader-clock ticks thread 0
@@ -20,17 +20,20 @@ PHASES = ["load", "minima sweep", "scans+neighbours+candidates", "walk1", "parit
 
 
 def main() -> int:
-    cfg = int(sys.argv[1]) if len(sys.argv) > 1 else 2
-    batch = int(sys.argv[2]) if len(sys.argv) > 2 else 1
+    args = [a for a in sys.argv[1:] if a != "--counts"]
+    counts = "--counts" in sys.argv[1:]        # loop-trip and per-lane counts instead of clean clock figures
+    cfg = int(args[0]) if len(args) > 0 else 2
+    batch = int(args[1]) if len(args) > 1 else 1
     import torch
 
     from . import _binding, build as hip_build
 
-    lib_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbpe_hip_trace.so")
+    lib_path = os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                            "libbpe_hip_counts.so" if counts else "libbpe_hip_trace.so")
     saved = hip_build.LIB
     hip_build.LIB = lib_path
     try:
-        hip_build.build(force=False, extra_flags=("-DBPE_TRACE",))   # only if missing or older than the sources
+        hip_build.build(force=False, extra_flags=("-DBPE_TRACE", "-DBPE_TRACE_COUNTS") if counts else ("-DBPE_TRACE",))   # only if missing or older than the sources
     finally:
         hip_build.LIB = saved
     _binding._LIB_PATH = lib_path
@@ -56,7 +59,13 @@ def main() -> int:
     lib.bpe_debug_trace(t.ctypes.data, 0)
     passes = max(int(t[10]), 1)
     print(f"config {cfg}, batch {batch}: {int(t[10])} passes, {int(t[11])} ticks in all")
+    if counts:
+        print(f"  loop trips of the wave: walk1 {int(t[12])}, walk2 {int(t[13])}, probe loop {int(t[8])};  "
+              f"summed over lanes: candidates {int(t[15])}, applied {int(t[16])}, look-ups {int(t[14])}")
+        return 0
     for name, v in zip(PHASES[:10], t[:10]):
+        if name == "refresh+publish":
+            continue
         per = f"{int(v) / passes:9.0f} / pass" if name not in ("load", "emit") else ""
         print(f"  {name:28s} {int(v):10d} ticks {100.0 * int(v) / max(int(t[11]), 1):5.1f} %  {per}")
     return 0
