@@ -118,6 +118,38 @@ __device__ inline uint32_t wave_scan(uint32_t v, uint32_t identity) {
   return v;
 }
 
+// Plain unsigned minimum, as an inclusive scan in lane order and as one in reverse lane order (a lane gets the
+// minimum over itself and all later lanes).  Each step is one v_min_u32 with a DPP operand, in place: a lane
+// that the step has no source for (or whose row is masked off) is simply not written.  The two wait states a
+// DPP read needs after the write of the same register are spelled out.
+#define BPE_DPP_MIN(v, ctrl) \
+  asm volatile("s_nop 1\n\tv_min_u32_dpp %0, %0, %0 " ctrl : "+v"(v))
+__device__ inline uint32_t wave_min_prefix(uint32_t v) {
+  BPE_DPP_MIN(v, "row_shr:1 row_mask:0xf bank_mask:0xf");
+  BPE_DPP_MIN(v, "row_shr:2 row_mask:0xf bank_mask:0xf");
+  BPE_DPP_MIN(v, "row_shr:4 row_mask:0xf bank_mask:0xf");
+  BPE_DPP_MIN(v, "row_shr:8 row_mask:0xf bank_mask:0xf");    // prefix minima inside each 16-lane row
+  BPE_DPP_MIN(v, "row_bcast:15 row_mask:0xa bank_mask:0xf");  // rows 1 and 3 take the total of the row before
+  BPE_DPP_MIN(v, "row_bcast:31 row_mask:0xc bank_mask:0xf");  // rows 2 and 3 take the total of lanes 0..31
+  return v;
+}
+// `not_row[r]` is 0 in the lanes of row r and all ones elsewhere (r = 0, 1, 2).
+__device__ inline uint32_t wave_min_suffix(uint32_t v, const uint32_t (&not_row)[3]) {
+  BPE_DPP_MIN(v, "row_shl:1 row_mask:0xf bank_mask:0xf");
+  BPE_DPP_MIN(v, "row_shl:2 row_mask:0xf bank_mask:0xf");
+  BPE_DPP_MIN(v, "row_shl:4 row_mask:0xf bank_mask:0xf");
+  BPE_DPP_MIN(v, "row_shl:8 row_mask:0xf bank_mask:0xf");    // suffix minima inside each 16-lane row
+  const uint32_t t1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);   // whole rows 1, 2, 3
+  const uint32_t t2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t t3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  const uint32_t s2 = min(t2, t3), s1 = min(t1, s2);         // what rows 1 and 0 still have to see
+  return min(min(v, s1 | not_row[0]), min(s2 | not_row[1], t3 | not_row[2]));
+}
+// The value the lane after mine holds (lane 63 receives `identity`).
+__device__ inline uint32_t wave_shift_down(uint32_t v, uint32_t identity) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x130, 0xF, 0xF, false);  // wave_shl:1
+}
+
 struct OpAdd { __device__ static uint32_t apply(uint32_t a, uint32_t b) { return a + b; } };
 
 // Run-parity element: bit 1 = "a run restarts inside", bit 0 = parity of the run length since the last

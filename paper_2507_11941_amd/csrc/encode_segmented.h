@@ -15,25 +15,25 @@
 //
 // Per pass a lane (a) sweeps its limits and values: running minima forward and backward inside its segments
 // give every position its segment minimum, except for the segment that enters the lane from the left and
-// the one that leaves it to the right; (b) those two are completed by a forward and a backward segmented
-// min-scan over the lanes (DPP; between waves through the LDS records); (c) compares each value with its
-// segment's horizon to get the candidate mask.  The rest of the pass is the same as in encode_string().
+// the one that leaves it to the right; (b) those two are completed by a prefix and a suffix minimum over the
+// lanes, made segment-aware by putting the number of cut-holding lanes so far above the limit in the key
+// (plain DPP minima; between waves through the LDS records); (c) compares each value with its segment's
+// horizon to get the candidate mask.  The rest of the pass is the same as in encode_string().
 #pragma once
 #include "encode_kernel.h"
 
 namespace bpe {
 
-constexpr uint32_t kInf31 = 0x7FFFFFFFu;    // "no pair" in the 31-bit domain of the horizons
-constexpr uint32_t kAll31 = 0x7FFFFFFEu;    // horizon above every rank
-constexpr uint32_t kReset31 = 0x80000000u;  // scan element flag: a cut lies inside this span
+// Horizons are limits in rank units, 20 bits: a pair (value v) is a candidate iff (v >> kRankShift) < horizon.
+constexpr uint32_t kInf20 = 0xFFFFFu;       // "no pair": equals kNoRank >> kRankShift, so it admits nothing
+constexpr uint32_t kAll20 = 0xFFFFEu;       // horizon above every rank (ranks stay below BPE_MAX_MERGES)
+constexpr uint32_t kInf31 = 0x7FFFFFFFu;    // identity of the cross-wave segmented minimum
+constexpr uint32_t kReset31 = 0x80000000u;  // cross-wave element flag: a cut lies inside this span
 
-// Horizons are kept in a "half-value" domain so that bit 31 is free for the scan flag and a pair value can
-// be compared with a horizon directly: half(limit) = limit << 11, and a pair is a candidate iff
-// (value >> 1) < half(limit), i.e. rank < limit.
-__device__ inline uint32_t half_limit_of(uint32_t value) {
-  if (value == kNoRank) return kInf31;
+__device__ inline uint32_t limit20_of(uint32_t value) {
+  if (value == kNoRank) return kInf20;
   const uint32_t lim = limit_of(value);
-  return lim >= 0xFFFFFu ? kAll31 : (lim << (kRankShift - 1));
+  return lim >= kAll20 ? kAll20 : lim;
 }
 
 // Segmented minimum: apply(left, right) = right if a cut lies inside right, else the minimum of the two with
@@ -114,7 +114,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           if (k + 1 < c0) cuts |= bit_at<mask_t>(k + 1);
         }
         V[k * W + tid] = v;
-        if (LIMITS) L[k * W + tid] = half_limit_of(v);
+        if (LIMITS) L[k * W + tid] = limit20_of(v);
         if (k < c0) {
           const uint32_t w = sh.byte_word[b[k + 1]];
           T[k * W + tid] = w;
@@ -128,6 +128,20 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     }
   }
   const uint64_t cut_first = __ballot((cuts & 1u) != 0);   // lanes whose column starts a segment (for good)
+  // cuts never move, so the grouping of the lanes for the horizon scans is fixed for the whole string
+  const uint64_t cut_lanes = __ballot(cuts != 0);
+  const uint32_t cuts_below = __builtin_amdgcn_mbcnt_hi((uint32_t)(cut_lanes >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)cut_lanes, 0u));
+  const uint32_t cuts_upto = cuts_below + (cuts ? 1u : 0u);                      // lanes <= me that hold a cut
+  const uint32_t cuts_from = (uint32_t)__builtin_popcountll(cut_lanes) - cuts_below;   // lanes >= me
+  const uint32_t fwd_group = (64u - cuts_upto) << 20, bwd_group = (64u - cuts_from) << 20;
+  uint32_t not_row[3];                                 // lane constants of the suffix scan, kept in registers
+  for (int r = 0; r < 3; ++r) {
+    not_row[r] = (lane >> 4) == r ? 0u : 0xFFFFFFFFu;
+    asm volatile("" : "+v"(not_row[r]));
+  }
+  const uint32_t cut_before = cuts_below ? kReset31 : 0u;                        // some lane before me has a cut
+  const uint32_t cut_after = cuts_from - (cuts ? 1u : 0u) ? kReset31 : 0u;       // some lane after me
   const int first_cut = cuts ? ctz_bits<mask_t>(cuts) : 32;
   const int last_cut = cuts ? top_bit<mask_t>(cuts) : 32;   // 32: none, every position belongs to the head
   TRACE_T(t_loaded);
@@ -153,21 +167,21 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         }
       }
     }
-    uint32_t run = kInf31;                             // forward: minimum since my last cut so far
+    uint32_t run = kInf20;                             // forward: minimum since my last cut so far
 #pragma unroll
     for (int g = 0; g < D; g += kGroup) {
       if (g < d) {
 #pragma unroll
         for (int k = g; k < g + kGroup; ++k) {
-          if (!LIMITS) e[k] = half_limit_of(v[k]);
+          if (!LIMITS) e[k] = limit20_of(v[k]);
           const uint32_t at_cut = (uint32_t)__builtin_amdgcn_sbfe((int)cuts, k, 1);   // all ones at a cut
-          run = min(run | at_cut, e[k]);               // a cut restarts the minimum (limits are < 2^31)
+          run = min(run | at_cut, e[k]);               // a cut restarts the minimum
           f[k] = run;
         }
       }
     }
-    const uint32_t tail_min = run & kInf31;            // over my positions from my last cut on (all, if none)
-    run = kInf31;                                      // backward: minimum up to the end of the segment
+    const uint32_t tail_min = run;                     // over my positions from my last cut on (all, if none)
+    run = kInf20;                                      // backward: minimum up to the end of the segment
 #pragma unroll
     for (int g = D - kGroup; g >= 0; g -= kGroup) {
       if (g < d) {
@@ -180,18 +194,17 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         }
       }
     }
-    const uint32_t head_min = min(run, kInf31);        // over my positions before my first cut (all, if none)
+    const uint32_t head_min = min(run, kInf20);        // over my positions before my first cut (all, if none)
     TRACE_T(t1);
     TRACE_ADD(1, t0, t1);
 
     // -- complete the segments that cross lanes: forward and backward segmented min-scans --
-    const uint32_t flag = cuts ? kReset31 : 0u;
-    const uint32_t fwd_inc = wave_scan<OpSegMin>(flag | tail_min, kInf31);
-    uint32_t in_fwd = wave_shift_up(fwd_inc, kInf31);
-    const uint32_t rev = lane_read(flag | head_min, 63 - lane);
-    const uint32_t bwd_inc_rev = wave_scan<OpSegMin>(rev, kInf31);
-    const uint32_t bwd_exc_rev = wave_shift_up(bwd_inc_rev, kInf31);
-    uint32_t in_bwd = lane_read(bwd_exc_rev, 63 - lane);
+    // A lane's key is (64 - number of lanes with a cut up to it) above the minimum: a plain minimum over the
+    // lanes before me then lands in the nearest group of lanes that share my segment, and picks its smallest.
+    const uint32_t fwd_inc = wave_min_prefix(fwd_group | tail_min);
+    const uint32_t bwd_inc = wave_min_suffix(bwd_group | head_min, not_row);
+    uint32_t in_fwd = (wave_shift_up(fwd_inc, 0xFFFFFFFFu) & kInf20) | cut_before;
+    uint32_t in_bwd = (wave_shift_down(bwd_inc, 0xFFFFFFFFu) & kInf20) | cut_after;
 
     // -- values just outside my column: the pair ending at my first token, the pair after my last --
     const uint64_t ne = __ballot(live != 0);
@@ -207,7 +220,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       any_pair = true;                                 // decided below from the candidate masks
     } else {
       // any pair in my wave: some position has a finite limit
-      uint32_t mine = kInf31;
+      uint32_t mine = kInf20;
 #pragma unroll
       for (int g = 0; g < D; g += kGroup) {
         if (g < d) {
@@ -215,11 +228,12 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           for (int k = g; k < g + kGroup; ++k) mine = min(mine, e[k]);
         }
       }
-      const uint64_t havep = __ballot(mine != kInf31);
+      const uint64_t havep = __ballot(mine != kInf20);
       const int fl = ne ? __builtin_ctzll(ne) : 0, ll = ne ? 63 - __builtin_clzll(ne) : 0;
       const uint32_t fv = lane_read(firstv, fl), ft = lane_read(ftok, fl), lv = lane_read(lastv, ll);
-      const uint32_t fwd_total = (uint32_t)__builtin_amdgcn_readlane((int)fwd_inc, 63);
-      const uint32_t bwd_total = (uint32_t)__builtin_amdgcn_readlane((int)bwd_inc_rev, 63);
+      const uint32_t wave_flag = cut_lanes ? kReset31 : 0u;
+      const uint32_t fwd_total = ((uint32_t)__builtin_amdgcn_readlane((int)fwd_inc, 63) & kInf20) | wave_flag;
+      const uint32_t bwd_total = ((uint32_t)__builtin_amdgcn_readlane((int)bwd_inc, 0) & kInf20) | wave_flag;
       if (lane == 0) {
         SegRecord r;
         r.fwd = fwd_total;
@@ -273,7 +287,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           uint32_t ek = (e_head & in_head) | (e[k] & ~in_head);
           ek = (e_tail & in_tail) | (ek & ~in_tail);
           // both sides are below 2^31, so the sign of the difference is the comparison
-          cm |= (((v[k] >> 1) - ek) >> 31) << k;
+          cm |= (((v[k] >> kRankShift) - ek) >> 31) << k;
         }
       }
     }
@@ -345,7 +359,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     const mask_t applied = cm & nbr & (pin ? (e0 ^ lr) : e0);
     // my first token is consumed if the pair ending at it is a candidate applied by the lane before me;
     // that pair belongs to the segment that enters my column
-    const bool skip_first = live != 0 && (in_val >> 1) < e_head && !(firstv < in_val) && pin == 0 && !(cuts & 1u);
+    const bool skip_first = live != 0 && (in_val >> kRankShift) < e_head && !(firstv < in_val) && pin == 0 && !(cuts & 1u);
     const bool touched = skip_first || applied != 0;
     mask_t dirty = 0;                                  // positions whose pair must be looked up again
     if (__ballot(touched)) {
@@ -353,13 +367,13 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         const int k = ctz_bits<mask_t>(m);
         T[k * W + tid] = merged_token_word(V[k * W + tid]);
         V[k * W + tid] = kNoRank;                      // until the new pair is looked up (if it needs to be)
-        if (LIMITS) L[k * W + tid] = kInf31;
+        if (LIMITS) L[k * W + tid] = kInf20;
         const mask_t upper = live & bits_above<mask_t>(k);
         if (upper) {                                   // the right operand is mine: it dies
           const int kn = ctz_bits<mask_t>(upper);
           live &= ~bit_at<mask_t>(kn);
           V[kn * W + tid] = kNoRank;
-          if (LIMITS) L[kn * W + tid] = kInf31;
+          if (LIMITS) L[kn * W + tid] = kInf20;
         }                                              // else it is the next lane's first token (skip_first there)
         dirty |= bit_at<mask_t>(k);
         const mask_t lower = live & bits_below<mask_t>(k);
@@ -369,7 +383,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         const int fk = ctz_bits<mask_t>(live);
         live &= ~bit_at<mask_t>(fk);
         V[fk * W + tid] = kNoRank;
-        if (LIMITS) L[fk * W + tid] = kInf31;
+        if (LIMITS) L[fk * W + tid] = kInf20;
       }
       dirty &= live;
       if (touched) ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
@@ -441,7 +455,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         if (k[j] >= 0) {
           const uint32_t nv = probe_finish(tab, pf[j]);
           V[k[j] * W + tid] = nv;
-          if (LIMITS) L[k[j] * W + tid] = half_limit_of(nv);
+          if (LIMITS) L[k[j] * W + tid] = limit20_of(nv);
         }
       }
     }
