@@ -153,45 +153,63 @@ __global__ __launch_bounds__(256) void pack_kernel(const int32_t* tmp_ids, const
 
 constexpr int kCutWindow = 128;
 
-// One workgroup: slots per string, their exclusive scan (slot_base), and the owner string of every slot.
+__device__ inline uint32_t slots_of(const int64_t* offsets, int s, int piece_target, int max_string) {
+  const int64_t len = offsets[s + 1] - offsets[s];
+  return (len <= 0 || len > max_string) ? 1u : (uint32_t)((len + piece_target - 1) / piece_target);
+}
+
+// Slots per string, their exclusive scan (slot_base), and the owner string of every slot.  Workgroup b owns
+// strings [1024 b, 1024 b + 1024): it counts the slots of all strings before its tile itself (the lengths are
+// 8 bytes per string and come from L2), scans its own tile, and fills the tile's stretch of slot_string by
+// binary search in the tile's prefix sums, one slot per thread and step.
 __global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offsets, int batch, int piece_target,
                                                            int max_string, Control* c, int32_t* slot_base,
                                                            int32_t* slot_string) {
   __shared__ uint32_t wave_sum[16];
-  __shared__ uint32_t carry_s;
+  __shared__ uint32_t first_s[1025];                   // slot_base of the tile's strings, relative to the tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) carry_s = 0;
-  if (tid < kBinKeys) { c->hist[tid] = 0; c->cursor[tid] = 0; }
-  if (tid < kMaxTiers) c->queue_head[tid] = 0;
-  __syncthreads();
-  for (int base = 0; base < batch; base += 1024) {
-    const int s = base + tid;
-    uint32_t m = 0;
-    if (s < batch) {
-      const int64_t len = offsets[s + 1] - offsets[s];
-      m = (len <= 0 || len > max_string) ? 1u : (uint32_t)((len + piece_target - 1) / piece_target);
-    }
-    uint32_t v = m;
-    for (int step = 1; step < 64; step <<= 1) {
-      const uint32_t o = (uint32_t)__shfl_up((int)v, step, 64);
-      if (lane >= step) v += o;
-    }
-    if (lane == 63) wave_sum[wave] = v;
-    __syncthreads();
-    uint32_t before = carry_s;
-    for (int w = 0; w < wave; ++w) before += wave_sum[w];
-    const uint32_t first = before + v - m;
-    if (s < batch) {
-      slot_base[s] = (int32_t)first;
-      for (uint32_t i = 0; i < m; ++i) slot_string[first + i] = s;
-    }
-    __syncthreads();
-    if (tid == 1023) carry_s = before + v;
-    __syncthreads();
+  const int base = blockIdx.x * 1024;
+  if (blockIdx.x == 0) {
+    if (tid < kBinKeys) { c->hist[tid] = 0; c->cursor[tid] = 0; }
+    if (tid < kMaxTiers) c->queue_head[tid] = 0;
   }
-  if (tid == 0) {
-    slot_base[batch] = (int32_t)carry_s;
-    c->n_slots = carry_s;
+  // slots of all strings before the tile
+  uint32_t before = 0;
+  for (int s = tid; s < base; s += 1024) before += slots_of(offsets, s, piece_target, max_string);
+  for (int step = 32; step >= 1; step >>= 1) before += (uint32_t)__shfl_xor((int)before, step, 64);
+  if (lane == 0) wave_sum[wave] = before;
+  __syncthreads();
+  uint32_t tile_first = 0;
+  for (int w = 0; w < 16; ++w) tile_first += wave_sum[w];
+  __syncthreads();
+  // the tile itself
+  const int s = base + tid;
+  const uint32_t m = s < batch ? slots_of(offsets, s, piece_target, max_string) : 0u;
+  uint32_t v = m;
+  for (int step = 1; step < 64; step <<= 1) {
+    const uint32_t o = (uint32_t)__shfl_up((int)v, step, 64);
+    if (lane >= step) v += o;
+  }
+  if (lane == 63) wave_sum[wave] = v;
+  __syncthreads();
+  uint32_t in_tile = v - m;
+  for (int w = 0; w < wave; ++w) in_tile += wave_sum[w];
+  first_s[tid] = in_tile;
+  if (tid == 1023) first_s[1024] = in_tile + m;
+  if (s < batch) slot_base[s] = (int32_t)(tile_first + in_tile);
+  __syncthreads();
+  const uint32_t tile_total = first_s[1024];
+  for (uint32_t g = tid; g < tile_total; g += 1024) {
+    int lo = 0, hi = 1023;                             // the last string of the tile whose first slot is <= g
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (first_s[mid] <= g) lo = mid; else hi = mid - 1;
+    }
+    slot_string[tile_first + g] = base + lo;
+  }
+  if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+    slot_base[batch] = (int32_t)(tile_first + tile_total);
+    c->n_slots = tile_first + tile_total;
   }
 }
 

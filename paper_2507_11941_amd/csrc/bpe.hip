@@ -374,7 +374,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
       const uint32_t* byte_pair =
           (const uint32_t*)((const char*)table->d_mem + table->bucket_bytes) + 256;
       const int per_slot_grid = (int)std::min<int64_t>((w.max_slots + 255) / 256, 65536);
-      hipLaunchKernelGGL(slot_layout_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, kPieceTarget,
+      hipLaunchKernelGGL(slot_layout_kernel, dim3((unsigned)((batch + 1023) / 1024)), dim3(1024), 0, stream, offsets, batch, kPieceTarget,
                          BPE_MAX_STRING_BYTES, ctrl, sb, ss);
       hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 3) / 4)), dim3(256), 0, stream, bytes,
                          offsets, byte_pair, kPieceTarget, BPE_MAX_STRING_BYTES, ctrl, sb, ss, pb);

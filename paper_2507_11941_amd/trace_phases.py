@@ -63,6 +63,8 @@ def main() -> int:
         print(f"  loop trips of the wave: walk1 {int(t[12])}, walk2 {int(t[13])}, probe loop {int(t[8])};  "
               f"summed over lanes: candidates {int(t[15])}, applied {int(t[16])}, look-ups {int(t[14])}")
         return 0
+    print(f"  inside the probe loop: operands from LDS {int(t[19])}, hash + loads + wait {int(t[17])}, "
+          f"compare + store {int(t[18])}")
     for name, v in zip(PHASES[:10], t[:10]):
         if name == "refresh+publish":
             continue
