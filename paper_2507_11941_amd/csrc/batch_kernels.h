@@ -393,16 +393,19 @@ __global__ __launch_bounds__(1024) void slot_offsets_kernel(const int32_t* count
   }
 }
 
-// One workgroup per slot: copy the piece's ids to their place in the dense output.
+// One wave per slot: copy the piece's ids to their place in the dense output.  (A piece has a few hundred ids;
+// what limits this kernel is the number of pieces whose descriptor loads are in flight, so waves, not
+// workgroups, take the pieces.)
 __global__ __launch_bounds__(256) void piece_pack_kernel(const int32_t* tmp_ids, const Control* c,
                                                          const int64_t* piece_begin, const int32_t* counts,
                                                          const int64_t* slot_out, int32_t* out_ids) {
   const uint32_t n_slots = c->n_slots;
-  for (uint32_t g = blockIdx.x; g < n_slots; g += gridDim.x) {
+  const int lane = threadIdx.x & 63;
+  for (uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6); g < n_slots; g += gridDim.x * 4) {
     const int k = counts[g];
     if (k <= 0) continue;
     const int64_t src = piece_begin[g], dst = slot_out[g];
-    for (int i = threadIdx.x; i < k; i += blockDim.x) out_ids[dst + i] = tmp_ids[src + i];
+    for (int i = lane; i < k; i += 64) out_ids[dst + i] = tmp_ids[src + i];
   }
 }
 

@@ -454,7 +454,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(64), 0, stream, tile_sum, w.n_tiles, ctrl, out_offsets, batch);
     hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
                        slot_string, slot_out, out_offsets);
-    const int grid = (int)std::min<int64_t>(w.max_slots, 262144);
+    const int grid = (int)std::min<int64_t>((w.max_slots + 3) / 4, 262144);
     hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
                        slot_out, out_ids);
   }
