@@ -33,7 +33,8 @@ enum {
   BPE_EDUPPAIR = -3,  /* the same (left,right) pair appears in two rows */
   BPE_ENOMEM = -4,    /* host or device allocation failed */
   BPE_EHIP = -5,      /* a HIP runtime call failed */
-  BPE_ETOOBIG = -6    /* more merges than the table format holds */
+  BPE_ETOOBIG = -6,   /* more merges than the table format holds */
+  BPE_EDUPID = -7     /* bpe_build_table_vocab: two tokens of the vocabulary share an id */
 };
 
 /* Largest string (bytes) bpe_encode_batch accepts, and largest number of merge rows a table holds. */
@@ -52,6 +53,19 @@ enum {
  * device and copies synchronously (this call is set-up, not hot path).
  */
 int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, int32_t* bad_row);
+
+/* Build the table over a vocabulary's own token ids (section 4.1: bytes are mapped to their initial token ids
+ * by lookup; section 5.1 runs a pretrained tokenizer's vocabulary, whose ids are not "byte value" and
+ * "256 + rank").  Same table, same encoding; only the numbering of the tokens differs:
+ *   byte_ids    HOST, int32[256]: id of the single-byte token of each byte value; all distinct, >= 0.
+ *   merges      HOST, int32[n_merges][2]: row r = (left_id, right_id) in vocabulary ids, rank r.  Each operand
+ *               must be a byte id or the merged id of an EARLIER row (else BPE_EBADMERGE, bad_row = r).
+ *   merged_ids  HOST, int32[n_merges]: id of the token row r creates; >= 0 and different from every byte id
+ *               and every other row's merged id (else BPE_EDUPID, bad_row = r; -1 if two bytes collide).
+ *   n_merges, out, bad_row: as for bpe_build_table.
+ * bpe_encode_batch on such a table writes vocabulary ids to out_ids.  The arrays are copied. */
+int bpe_build_table_vocab(const int32_t* byte_ids, const int32_t* merges, const int32_t* merged_ids,
+                          int32_t n_merges, bpe_table** out, int32_t* bad_row);
 
 /* Release a table.  NULL is allowed.  The caller must have drained every stream that uses it. */
 void bpe_free_table(bpe_table* table);

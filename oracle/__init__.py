@@ -37,6 +37,8 @@ def _load():
         vp, i32, i64, ci = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int
         lib.orc_table_new.argtypes = [vp, i32]
         lib.orc_table_new.restype = vp
+        lib.orc_table_new_vocab.argtypes = [vp, vp, vp, i32]
+        lib.orc_table_new_vocab.restype = vp
         lib.orc_table_free.argtypes = [vp]
         lib.orc_table_free.restype = None
         lib.orc_encode.argtypes = [vp, ci, vp, i64, vp, vp]
@@ -60,11 +62,24 @@ def _as_bytes(s) -> np.ndarray:
 
 
 class Table:
-    """A merge table: rows of (left_id, right_id); rank = row index; merged id = 256 + rank."""
+    """A merge table: rows of (left_id, right_id); rank = row index; merged id = 256 + rank.
 
-    def __init__(self, merges):
+    With a vocabulary (`byte_ids[256]`: id of each single byte; `merged_ids[rows]`: id of the token each row
+    creates) the rows and the results are in the vocabulary's ids instead."""
+
+    def __init__(self, merges, byte_ids=None, merged_ids=None):
         self.merges = np.ascontiguousarray(np.asarray(merges, dtype=np.int32).reshape(-1, 2))
-        self._h = _load().orc_table_new(self.merges.ctypes.data, len(self.merges))
+        if (byte_ids is None) != (merged_ids is None):
+            raise ValueError("give both byte_ids and merged_ids, or neither")
+        if byte_ids is None:
+            self._h = _load().orc_table_new(self.merges.ctypes.data, len(self.merges))
+        else:
+            self.byte_ids = np.ascontiguousarray(np.asarray(byte_ids, dtype=np.int32))
+            self.merged_ids = np.ascontiguousarray(np.asarray(merged_ids, dtype=np.int32))
+            if self.byte_ids.shape != (256,) or self.merged_ids.shape != (len(self.merges),):
+                raise ValueError("byte_ids must have 256 entries and merged_ids one per row")
+            self._h = _load().orc_table_new_vocab(self.byte_ids.ctypes.data, self.merges.ctypes.data,
+                                                  self.merged_ids.ctypes.data, len(self.merges))
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

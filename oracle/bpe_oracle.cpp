@@ -19,7 +19,7 @@
 //   * encode_heap        -- the priority-queue scheme section 3.2 attributes to CPU libraries
 //                           (O(n log n)): heap of (rank, position) over a doubly linked token list.  Used
 //                           only where the quadratic encoders are too slow; admitted by agreeing with them.
-//   * decode             -- expands ids back to bytes (id < 256 is a byte, id = 256 + r is row r's pair).
+//   * decode             -- expands ids back to bytes (a byte's id is a byte, a row's id is the row's pair).
 //   * train / train_naive-- greedy most-frequent-pair trainer.  The paper uses pretrained tables
 //                           (sections 5.1, 5.2), so the trainer is this build's own definition:
 //                           chunk the corpus before every whitespace byte (space, tab, LF, CR), count
@@ -29,7 +29,9 @@
 //                           merged id = 256 + rank), apply it in every chunk left to right without overlap.
 //
 // Conventions: a merge table is n rows of (left_id, right_id) int32; token ids are int32; a string is any
-// byte sequence (byte-level pre-tokenisation, section 4.1: initial id = byte value).
+// byte sequence (byte-level pre-tokenisation, section 4.1: initial id = the vocabulary's id of the byte, the
+// byte value itself unless a vocabulary is given; a row's merged token is 256 + rank unless a vocabulary
+// names it).
 //
 // Parity pins (tests/test_oracle_*.py): hand-worked examples, closed forms for doubling chains and
 // alternating pairs, brute force on exhaustive small alphabets, round trip and fixed-point invariants.
@@ -59,6 +61,17 @@ struct Table {
   std::vector<std::pair<int32_t, int32_t>> rows;   // row index = rank
   std::unordered_map<uint64_t, int32_t> rank;      // (a,b) -> rank     (map R of Algorithm 1)
   std::map<std::pair<int32_t, int32_t>, int32_t> rank_ordered;  // same content, used by the brute force
+  // Vocabulary (section 4.1: bytes are mapped to their initial token ids by lookup; a merge yields the id the
+  // vocabulary gives the merged token).  Default: byte b has id b, row r creates id 256 + r.
+  int32_t byte_id[256];
+  std::vector<int32_t> merged_id;                  // [rows]
+  std::unordered_map<int32_t, int32_t> byte_of_id, row_of_id;   // inverse, for decode
+
+  std::vector<int32_t> initial(const uint8_t* s, int64_t n) const {   // "split S into a list of bytes"
+    std::vector<int32_t> T((size_t)n);
+    for (int64_t i = 0; i < n; ++i) T[(size_t)i] = byte_id[s[i]];
+    return T;
+  }
 
   int32_t lookup(int32_t a, int32_t b) const {
     auto it = rank.find(pair_key(a, b));
@@ -69,7 +82,7 @@ struct Table {
 // ---------------------------------------------------------------------------------------------------
 // Algorithm 1, literally.
 std::vector<int32_t> encode_bruteforce(const Table& t, const uint8_t* s, int64_t n) {
-  std::vector<int32_t> T(s, s + n);                       // split S into a list of bytes
+  std::vector<int32_t> T = t.initial(s, n);               // split S into a list of bytes
   while (true) {
     int32_t best = kNoRank;
     std::pair<int32_t, int32_t> best_pair{0, 0};
@@ -83,7 +96,7 @@ std::vector<int32_t> encode_bruteforce(const Table& t, const uint8_t* s, int64_t
     if (best == kNoRank) break;                            // no pair of T is in the table
     for (size_t i = 0; i + 1 < T.size(); ++i) {           // left-most occurrence of (a,b)
       if (T[i] == best_pair.first && T[i + 1] == best_pair.second) {
-        T[i] = 256 + best;
+        T[i] = t.merged_id[(size_t)best];
         T.erase(T.begin() + (std::ptrdiff_t)i + 1);
         break;
       }
@@ -94,7 +107,7 @@ std::vector<int32_t> encode_bruteforce(const Table& t, const uint8_t* s, int64_t
 
 // Textbook sequential encoder: cached ranks, one merge per iteration.
 std::vector<int32_t> encode_textbook(const Table& t, const uint8_t* s, int64_t n) {
-  std::vector<int32_t> T(s, s + n);
+  std::vector<int32_t> T = t.initial(s, n);
   std::vector<int32_t> R;                                  // R[i] = rank of (T[i], T[i+1])
   for (size_t i = 0; i + 1 < T.size(); ++i) R.push_back(t.lookup(T[i], T[i + 1]));
   while (true) {
@@ -104,7 +117,7 @@ std::vector<int32_t> encode_textbook(const Table& t, const uint8_t* s, int64_t n
       if (R[i] < best) { best = R[i]; at = i; }            // strict <: first index wins ties
     }
     if (best == kNoRank) break;
-    T[at] = 256 + best;
+    T[at] = t.merged_id[(size_t)best];
     T.erase(T.begin() + (std::ptrdiff_t)at + 1);
     R.erase(R.begin() + (std::ptrdiff_t)at);               // the pair that was merged
     if (at > 0) R[at - 1] = t.lookup(T[at - 1], T[at]);
@@ -121,7 +134,7 @@ struct PassStats {
 
 // Pass view of section 4.2: one rank per pass, every non-overlapping occurrence, left-most first.
 std::vector<int32_t> encode_passes(const Table& t, const uint8_t* s, int64_t n, PassStats* st) {
-  std::vector<int32_t> T(s, s + n);
+  std::vector<int32_t> T = t.initial(s, n);
   while (true) {
     int32_t best = kNoRank;
     for (size_t i = 0; i + 1 < T.size(); ++i) best = std::min(best, t.lookup(T[i], T[i + 1]));
@@ -133,7 +146,7 @@ std::vector<int32_t> encode_passes(const Table& t, const uint8_t* s, int64_t n, 
     size_t i = 0;
     while (i < T.size()) {
       if (i + 1 < T.size() && T[i] == a && T[i + 1] == b) {
-        next.push_back(256 + best);
+        next.push_back(t.merged_id[(size_t)best]);
         i += 2;                                            // the right token is consumed
         if (st) st->merges += 1;
       } else {
@@ -152,7 +165,7 @@ std::vector<int32_t> encode_heap(const Table& t, const uint8_t* s, int64_t n) {
     int32_t rank; int64_t left; int64_t right; int32_t a; int32_t b;
     bool operator>(const Entry& o) const { return rank != o.rank ? rank > o.rank : left > o.left; }
   };
-  std::vector<int32_t> tok(s, s + n);
+  std::vector<int32_t> tok = t.initial(s, n);
   std::vector<int64_t> prev((size_t)n), next((size_t)n);
   std::vector<uint8_t> alive((size_t)n, 1);
   for (int64_t i = 0; i < n; ++i) { prev[(size_t)i] = i - 1; next[(size_t)i] = i + 1 < n ? i + 1 : -1; }
@@ -172,7 +185,7 @@ std::vector<int32_t> encode_heap(const Table& t, const uint8_t* s, int64_t n) {
     if (!alive[(size_t)e.left] || !alive[(size_t)e.right]) continue;
     if (next[(size_t)e.left] != e.right) continue;
     if (tok[(size_t)e.left] != e.a || tok[(size_t)e.right] != e.b) continue;
-    tok[(size_t)e.left] = 256 + e.rank;
+    tok[(size_t)e.left] = t.merged_id[(size_t)e.rank];
     alive[(size_t)e.right] = 0;
     int64_t rr = next[(size_t)e.right];
     next[(size_t)e.left] = rr;
@@ -186,8 +199,9 @@ std::vector<int32_t> encode_heap(const Table& t, const uint8_t* s, int64_t n) {
 }
 
 void decode_id(const Table& t, int32_t id, std::string& out) {
-  if (id < 256) { out.push_back((char)id); return; }
-  const auto& row = t.rows[(size_t)(id - 256)];
+  auto b = t.byte_of_id.find(id);
+  if (b != t.byte_of_id.end()) { out.push_back((char)b->second); return; }
+  const auto& row = t.rows[(size_t)t.row_of_id.at(id)];
   decode_id(t, row.first, out);
   decode_id(t, row.second, out);
 }
@@ -348,15 +362,29 @@ int64_t train(const uint8_t* c, int64_t n, int32_t n_merges, int32_t* out) {
 
 extern "C" {
 
-void* orc_table_new(const int32_t* merges, int32_t n_merges) {
+// Table over a vocabulary: byte_ids[256] are the ids of the single bytes, row r = (left id, right id) in
+// vocabulary ids, merged_ids[r] the id of the token it creates.  Null byte_ids / merged_ids mean the default
+// numbering (byte b -> b, row r -> 256 + r).
+void* orc_table_new_vocab(const int32_t* byte_ids, const int32_t* merges, const int32_t* merged_ids,
+                          int32_t n_merges) {
   Table* t = new Table();
+  for (int b = 0; b < 256; ++b) {
+    t->byte_id[b] = byte_ids ? byte_ids[b] : b;
+    t->byte_of_id.emplace(t->byte_id[b], b);
+  }
   for (int32_t r = 0; r < n_merges; ++r) {
     int32_t a = merges[2 * r], b = merges[2 * r + 1];
     t->rows.push_back({a, b});
     t->rank.emplace(pair_key(a, b), r);                    // first row wins if a pair repeats
     t->rank_ordered.emplace(std::make_pair(a, b), r);
+    t->merged_id.push_back(merged_ids ? merged_ids[r] : 256 + r);
+    t->row_of_id.emplace(t->merged_id.back(), r);
   }
   return t;
+}
+
+void* orc_table_new(const int32_t* merges, int32_t n_merges) {
+  return orc_table_new_vocab(nullptr, merges, nullptr, n_merges);
 }
 
 void orc_table_free(void* h) { delete (Table*)h; }

@@ -39,6 +39,8 @@ def load_library():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.bpe_build_table.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(i32)]
     lib.bpe_build_table.restype = ctypes.c_int
+    lib.bpe_build_table_vocab.argtypes = [vp, vp, vp, i32, ctypes.POINTER(vp), ctypes.POINTER(i32)]
+    lib.bpe_build_table_vocab.restype = ctypes.c_int
     lib.bpe_free_table.argtypes = [vp]
     lib.bpe_free_table.restype = None
     lib.bpe_table_n_merges.argtypes = [vp]
@@ -94,6 +96,25 @@ def build_table(merges) -> Table:
     code = lib.bpe_build_table(m.ctypes.data if len(m) else None, len(m), ctypes.byref(handle), ctypes.byref(bad))
     if code != 0:
         raise BpeError(code, "bpe_build_table", f"{lib.bpe_strerror(code).decode()} (row {bad.value})")
+    return Table(handle.value, len(m))
+
+
+def build_table_vocab(byte_ids, merges, merged_ids) -> Table:
+    """Table over a vocabulary's own ids: byte_ids int32[256], merges int32[n, 2] in vocabulary ids,
+    merged_ids int32[n] (id of the token each row creates); encode_batch then returns vocabulary ids."""
+    lib = load_library()
+    b = np.ascontiguousarray(np.asarray(byte_ids, dtype=np.int32))
+    m = np.ascontiguousarray(np.asarray(merges, dtype=np.int32).reshape(-1, 2))
+    g = np.ascontiguousarray(np.asarray(merged_ids, dtype=np.int32))
+    if b.shape != (256,) or g.shape != (len(m),):
+        raise ValueError("byte_ids must have 256 entries and merged_ids one per row")
+    handle = ctypes.c_void_p()
+    bad = ctypes.c_int32(-1)
+    code = lib.bpe_build_table_vocab(b.ctypes.data, m.ctypes.data if len(m) else None,
+                                     g.ctypes.data if len(m) else None, len(m), ctypes.byref(handle),
+                                     ctypes.byref(bad))
+    if code != 0:
+        raise BpeError(code, "bpe_build_table_vocab", f"{lib.bpe_strerror(code).decode()} (row {bad.value})")
     return Table(handle.value, len(m))
 
 

@@ -108,11 +108,17 @@ __global__ __launch_bounds__(1024) void offsets_scan_kernel(const int32_t* count
   }
 }
 
+// The encode kernels number tokens their own way (byte b = b, row r creates 256 + r); a table built over a
+// vocabulary carries the vocabulary's id of each, applied where the ids are written to the output.
+__device__ inline int32_t vocabulary_id(const int32_t* id_map, int32_t token) {
+  return id_map ? id_map[token] : token;
+}
+
 // Small batches: offsets and packing in one launch.  Workgroup s sums the counts before its string itself
 // (the batch is at most a few thousand strings), writes out_offsets[s] and copies the string's ids.
 __global__ __launch_bounds__(256) void scan_pack_kernel(const int32_t* tmp_ids, const int64_t* offsets,
                                                         const int32_t* counts, int batch, int64_t* out_offsets,
-                                                        int32_t* out_ids) {
+                                                        int32_t* out_ids, const int32_t* id_map) {
   __shared__ int64_t wave_sum[4];
   const int s = blockIdx.x;
   int64_t v = 0;
@@ -127,16 +133,17 @@ __global__ __launch_bounds__(256) void scan_pack_kernel(const int32_t* tmp_ids, 
     if (s == batch - 1) out_offsets[batch] = dst + k;
   }
   const int64_t src = offsets[s];
-  for (int i = threadIdx.x; i < k; i += 256) out_ids[dst + i] = tmp_ids[src + i];
+  for (int i = threadIdx.x; i < k; i += 256) out_ids[dst + i] = vocabulary_id(id_map, tmp_ids[src + i]);
 }
 
 // One workgroup per string: copy its ids from the per-string staging area to the dense output.
 __global__ __launch_bounds__(256) void pack_kernel(const int32_t* tmp_ids, const int64_t* offsets,
-                                                   const int64_t* out_offsets, int batch, int32_t* out_ids) {
+                                                   const int64_t* out_offsets, int batch, int32_t* out_ids,
+                                                   const int32_t* id_map) {
   for (int s = blockIdx.x; s < batch; s += gridDim.x) {
     const int64_t src = offsets[s], dst = out_offsets[s];
     const int k = (int)(out_offsets[s + 1] - dst);
-    for (int i = threadIdx.x; i < k; i += blockDim.x) out_ids[dst + i] = tmp_ids[src + i];
+    for (int i = threadIdx.x; i < k; i += blockDim.x) out_ids[dst + i] = vocabulary_id(id_map, tmp_ids[src + i]);
   }
 }
 
@@ -398,14 +405,15 @@ __global__ __launch_bounds__(1024) void slot_offsets_kernel(const int32_t* count
 // workgroups, take the pieces.)
 __global__ __launch_bounds__(256) void piece_pack_kernel(const int32_t* tmp_ids, const Control* c,
                                                          const int64_t* piece_begin, const int32_t* counts,
-                                                         const int64_t* slot_out, int32_t* out_ids) {
+                                                         const int64_t* slot_out, int32_t* out_ids,
+                                                         const int32_t* id_map) {
   const uint32_t n_slots = c->n_slots;
   const int lane = threadIdx.x & 63;
   for (uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6); g < n_slots; g += gridDim.x * 4) {
     const int k = counts[g];
     if (k <= 0) continue;
     const int64_t src = piece_begin[g], dst = slot_out[g];
-    for (int i = lane; i < k; i += 64) out_ids[dst + i] = tmp_ids[src + i];
+    for (int i = lane; i < k; i += 64) out_ids[dst + i] = vocabulary_id(id_map, tmp_ids[src + i]);
   }
 }
 

@@ -8,6 +8,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/bpe.h"
@@ -22,8 +23,10 @@ struct bpe_table {
   int device = 0;
   int32_t n_merges = 0;
   int log2_buckets = 0;
-  void* d_mem = nullptr;          // buckets, then the 256 byte token words, then the 256 x 256 byte-pair values
+  void* d_mem = nullptr;          // buckets, then the 256 byte token words, then the 256 x 256 byte-pair values,
+                                  // then (tables over a vocabulary only) the id of every token, int32[256 + rows]
   size_t bucket_bytes = 0;
+  const int32_t* d_id_map = nullptr;   // inside d_mem; null: byte b is id b, row r creates id 256 + r
 };
 
 namespace {
@@ -191,12 +194,14 @@ bool g_profiling = false;
 
 extern "C" {
 
-int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, int32_t* bad_row) {
-  if (bad_row) *bad_row = -1;
-  if (!out) return BPE_EINVAL;
-  *out = nullptr;
-  if (n_merges < 0 || (n_merges > 0 && !merges)) return BPE_EINVAL;
-  if (n_merges > BPE_MAX_MERGES) return BPE_ETOOBIG;
+}  // extern "C"
+
+namespace {
+
+// merges: rows in the library's own numbering (byte b = b, row r creates 256 + r); id_map: null, or the
+// vocabulary id of each of the 256 + n_merges tokens, which the packing kernels then write instead.
+int build_table(const int32_t* merges, int32_t n_merges, const int32_t* id_map, bpe_table** out,
+                int32_t* bad_row) {
 
   // operands must exist before the row that uses them
   for (int32_t r = 0; r < n_merges; ++r) {
@@ -302,15 +307,76 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
   t->log2_buckets = log2_buckets;
   t->bucket_bytes = n_words * sizeof(uint32_t);
   if (hipGetDevice(&t->device) != hipSuccess) { delete t; return BPE_EHIP; }
-  hipError_t e = hipMalloc(&t->d_mem, host.size() * sizeof(uint32_t));
+  const size_t map_words = id_map ? (size_t)n_merges + 256 : 0;
+  hipError_t e = hipMalloc(&t->d_mem, (host.size() + map_words) * sizeof(uint32_t));
   if (e != hipSuccess) { delete t; return e == hipErrorOutOfMemory ? BPE_ENOMEM : BPE_EHIP; }
-  if (hipMemcpy(t->d_mem, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) {
+  bool ok = hipMemcpy(t->d_mem, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
+  if (ok && id_map) {
+    int32_t* d_map = (int32_t*)((uint32_t*)t->d_mem + host.size());
+    ok = hipMemcpy(d_map, id_map, map_words * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+    t->d_id_map = d_map;
+  }
+  if (!ok) {
     (void)hipFree(t->d_mem);
     delete t;
     return BPE_EHIP;
   }
   *out = t;
   return BPE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, int32_t* bad_row) {
+  if (bad_row) *bad_row = -1;
+  if (!out) return BPE_EINVAL;
+  *out = nullptr;
+  if (n_merges < 0 || (n_merges > 0 && !merges)) return BPE_EINVAL;
+  if (n_merges > BPE_MAX_MERGES) return BPE_ETOOBIG;
+  return build_table(merges, n_merges, nullptr, out, bad_row);
+}
+
+int bpe_build_table_vocab(const int32_t* byte_ids, const int32_t* merges, const int32_t* merged_ids,
+                          int32_t n_merges, bpe_table** out, int32_t* bad_row) {
+  if (bad_row) *bad_row = -1;
+  if (!out) return BPE_EINVAL;
+  *out = nullptr;
+  if (!byte_ids || n_merges < 0 || (n_merges > 0 && (!merges || !merged_ids))) return BPE_EINVAL;
+  if (n_merges > BPE_MAX_MERGES) return BPE_ETOOBIG;
+  // vocabulary id -> the library's own number of the token (byte b = b, row r = 256 + r), filled row by row
+  // so that a row can only name tokens that exist before it
+  std::vector<int32_t> id_map, own;
+  std::unordered_map<int32_t, int32_t> number_of;
+  try {
+    id_map.resize((size_t)n_merges + 256);
+    own.resize((size_t)n_merges * 2);
+    number_of.reserve((size_t)n_merges + 256);
+    for (int b = 0; b < 256; ++b) {
+      if (byte_ids[b] < 0) return BPE_EINVAL;
+      if (!number_of.emplace(byte_ids[b], b).second) return BPE_EDUPID;     // two bytes share an id
+      id_map[(size_t)b] = byte_ids[b];
+    }
+    for (int32_t r = 0; r < n_merges; ++r) {
+      for (int side = 0; side < 2; ++side) {
+        const auto it = number_of.find(merges[2 * r + side]);
+        if (it == number_of.end()) {                           // not a byte, not created by an earlier row
+          if (bad_row) *bad_row = r;
+          return BPE_EBADMERGE;
+        }
+        own[(size_t)(2 * r + side)] = it->second;
+      }
+      if (merged_ids[r] < 0 || !number_of.emplace(merged_ids[r], 256 + r).second) {
+        if (bad_row) *bad_row = r;
+        return merged_ids[r] < 0 ? BPE_EINVAL : BPE_EDUPID;    // the id already names another token
+      }
+      id_map[(size_t)(256 + r)] = merged_ids[r];
+    }
+  } catch (const std::bad_alloc&) {
+    return BPE_ENOMEM;
+  }
+  return build_table(own.data(), n_merges, id_map.data(), out, bad_row);
 }
 
 void bpe_free_table(bpe_table* table) {
@@ -440,12 +506,13 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   }
   if (!w.split && batch > 0 && batch <= 4096) {
     hipLaunchKernelGGL(scan_pack_kernel, dim3(batch), dim3(256), 0, stream, tmp_ids, offsets, counts, batch,
-                       out_offsets, out_ids);
+                       out_offsets, out_ids, table->d_id_map);
   } else if (!w.split) {
     hipLaunchKernelGGL(offsets_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, batch, out_offsets);
     if (batch > 0) {
       const int grid = batch < 65536 ? batch : 65536;
-      hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, offsets, out_offsets, batch, out_ids);
+      hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, offsets, out_offsets, batch, out_ids,
+                         table->d_id_map);
     }
   } else {
     int64_t* tile_sum = (int64_t*)(ws + w.tile_sum);
@@ -456,7 +523,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
                        slot_string, slot_out, out_offsets);
     const int grid = (int)std::min<int64_t>((w.max_slots + 3) / 4, 262144);
     hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
-                       slot_out, out_ids);
+                       slot_out, out_ids, table->d_id_map);
   }
   return hipGetLastError() == hipSuccess ? BPE_OK : BPE_EHIP;
 }
@@ -504,6 +571,7 @@ const char* bpe_strerror(int code) {
     case BPE_ENOMEM: return "out of memory";
     case BPE_EHIP: return "HIP runtime call failed";
     case BPE_ETOOBIG: return "too many merge rows for the table format";
+    case BPE_EDUPID: return "two tokens of the vocabulary share an id";
     default: return "unknown error";
   }
 }

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_error_strings():
     lib = bpe.load_library()
-    for code in (0, -1, -2, -3, -4, -5, -6):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
         assert lib.bpe_strerror(code)
     assert lib.bpe_strerror(0) == b"ok"
 
@@ -55,6 +55,40 @@ def test_build_table_rejects_malformed_tables_on_the_host():
     assert lib.bpe_build_table(None, 1, None, None) == -1
     with pytest.raises(bpe.BpeError):
         bpe.build_table([(97, 98), (97, 98)])
+
+
+def build_vocab_raw(byte_ids, merges, merged):
+    lib = bpe.load_library()
+    b = np.ascontiguousarray(byte_ids, dtype=np.int32)
+    m = np.ascontiguousarray(np.asarray(merges, dtype=np.int32).reshape(-1, 2))
+    g = np.ascontiguousarray(merged, dtype=np.int32)
+    handle, bad = ctypes.c_void_p(), ctypes.c_int32(-7)
+    code = lib.bpe_build_table_vocab(b.ctypes.data, m.ctypes.data, g.ctypes.data, len(m), ctypes.byref(handle),
+                                     ctypes.byref(bad))
+    return code, bad.value
+
+
+def test_build_table_vocab_rejects_malformed_vocabularies_on_the_host():
+    ids = np.arange(256, dtype=np.int32) + 1000
+    a, b, c = 1097, 1098, 1099
+    # an operand that is neither a byte id nor created by an earlier row
+    assert build_vocab_raw(ids, [(a, b), (7, c)], [5, 6]) == (-2, 1)
+    assert build_vocab_raw(ids, [(5, b)], [5]) == (-2, 0)           # a row cannot use its own token
+    assert build_vocab_raw(ids, [(97, 98)], [5]) == (-2, 0)         # default byte values are not ids here
+    # ids must be unique: merged id equal to a byte id, to an earlier merged id, two bytes alike
+    assert build_vocab_raw(ids, [(a, b)], [a]) == (-7, 0)
+    assert build_vocab_raw(ids, [(a, b), (b, c)], [5, 5]) == (-7, 1)
+    twice = ids.copy()
+    twice[3] = twice[200]
+    assert build_vocab_raw(twice, [(a, b)], [5]) == (-7, -1)
+    # the same pair in two rows
+    assert build_vocab_raw(ids, [(a, b), (b, c), (a, b)], [5, 6, 7]) == (-3, 2)
+    # negative ids, null arrays
+    assert build_vocab_raw(ids, [(a, b)], [-5])[0] == -1
+    lib = bpe.load_library()
+    assert lib.bpe_build_table_vocab(None, None, None, 0, None, None) == -1
+    with pytest.raises(bpe.BpeError):
+        bpe.build_table_vocab(ids, [(a, b)], [a])
 
 
 def test_workspace_bytes():

@@ -68,6 +68,30 @@ def test_config_full_size(bpe, cfg):
     assert ids.max() < 256 + len(merges)
 
 
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_config_under_a_vocabulary(bpe, cfg):
+    """The same batches with the tokens renamed by a random injection (a vocabulary's own ids): all three
+    packing paths write vocabulary ids, compared with the oracle built over that vocabulary."""
+    c = workloads.CONFIGS[cfg]
+    merges = workloads.load_merges(c.table)
+    rng = np.random.default_rng(2024 + cfg)
+    phi = rng.permutation(3 * (256 + len(merges)))[: 256 + len(merges)].astype(np.int32)
+    named = phi[merges]
+    table = bpe.build_table_vocab(phi[:256], named, phi[256:])
+    orc = oracle.Table(named, phi[:256], phi[256:])
+    data, off = workloads.batch(cfg)
+    ids, out_off = gpu_encode(table, data, off)
+    want_ids, want_off = orc.encode_batch(data, off, tier=oracle.HEAP, nthreads=ORACLE_THREADS)
+    assert_same_encoding(ids, out_off, want_ids, want_off, f"config {cfg} under a vocabulary")
+    # a batch above 4096 strings of at most 1 KiB takes the third packing path
+    if cfg == 2:
+        many, many_off = workloads.batch(cfg, batch_override=5000)
+        ids, out_off = gpu_encode(table, many, many_off)
+        want_ids, want_off = orc.encode_batch(many, many_off, tier=oracle.HEAP, nthreads=ORACLE_THREADS)
+        assert_same_encoding(ids, out_off, want_ids, want_off, "5000 strings under a vocabulary")
+    table.free()
+
+
 def test_ragged_lengths_and_unaligned_starts(bpe):
     """Lengths 0..~70 around every kernel-variant boundary, cut from one text stream so starts are unaligned."""
     table, orc, _ = tables(bpe, "100k")

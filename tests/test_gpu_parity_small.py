@@ -135,3 +135,48 @@ def test_encode_rejects_bad_arguments(bpe):
     with pytest.raises(bpe.BpeError):
         bpe.encode_batch(table, data, offsets, max_len=16, workspace=short)
     torch.cuda.synchronize()
+
+
+def parse_vocab(byte_spec, row_spec):
+    byte_ids = np.arange(256, dtype=np.int32) + 1000
+    for item in byte_spec.split(","):
+        ch, val = item.split("=")
+        byte_ids[ord(ch)] = int(val)
+    merges, merged = [], []
+    for item in row_spec.split(","):
+        pair, m = item.split(">")
+        l, r = pair.split(":")
+        merges.append((int(l), int(r)))
+        merged.append(int(m))
+    return byte_ids, merges, merged
+
+
+def test_hand_worked_vocab_examples(bpe):
+    by_table = {}
+    for row in read_golden("hand_worked_vocab.txt"):
+        by_table.setdefault((row[0], row[1]), []).append((row[2].encode(), parse_ids(row[3])))
+    for (byte_spec, row_spec), cases in by_table.items():
+        table = bpe.build_table_vocab(*parse_vocab(byte_spec, row_spec))
+        ids, out_off = gpu_encode(table, *to_batch([c[0] for c in cases]))
+        for i, (text, want) in enumerate(cases):
+            assert ids[out_off[i]:out_off[i + 1]].tolist() == want, (byte_spec, row_spec, text)
+        table.free()
+
+
+def test_random_vocabularies(bpe):
+    """Random tables under a random renaming of the tokens, against the oracle built over the same vocabulary."""
+    rng = random.Random(4321)
+    for trial in range(12):
+        alphabet = rng.sample(range(256), rng.randint(2, 6))
+        rows = random_monotone_table(rng, rng.randint(1, 60), alphabet)
+        phi = np.array(rng.sample(range(4 * (256 + len(rows))), 256 + len(rows)), dtype=np.int32)
+        named = [(int(phi[a]), int(phi[b])) for a, b in rows]
+        orc = oracle.Table(named, phi[:256], phi[256:])
+        table = bpe.build_table_vocab(phi[:256], named, phi[256:])
+        strings = [bytes(rng.choice(alphabet) for _ in range(rng.choice([0, 1, 2, 5, 64, 65, 300, 1100, 2500])))
+                   for _ in range(40)]
+        data, off = to_batch(strings)
+        ids, out_off = gpu_encode(table, data, off)
+        want_ids, want_off = orc.encode_batch(data, off, tier=oracle.TEXTBOOK, nthreads=8)
+        assert_same_encoding(ids, out_off, want_ids, want_off, f"vocabulary trial {trial}")
+        table.free()
