@@ -54,6 +54,17 @@ enum {
  */
 int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, int32_t* bad_row);
 
+/* The table bpe_build_table would upload, built in HOST memory instead (no device is touched): for callers
+ * that want to inspect or cache it, and for tests of the builder.  Layout, in uint32 words:
+ *   [buckets: 2^log2_buckets x 4 slots x {value, tag}] [token word of each byte: 256] [byte-pair table: 65536]
+ * (section 4.3's hashmap; the format is described in paper_2507_11941_amd/csrc/table_format.h).
+ *   merges, n_merges, bad_row  as for bpe_build_table (same validation, same codes).
+ *   words         HOST, uint32[capacity]; may be NULL when capacity is 0 (size query).
+ *   log2_buckets  HOST, may be NULL; receives log2 of the number of buckets.
+ * Returns the number of words of the image (written only if it fits `capacity`), or a negative BPE_* code. */
+int64_t bpe_table_image(const int32_t* merges, int32_t n_merges, uint32_t* words, int64_t capacity,
+                        int32_t* log2_buckets, int32_t* bad_row);
+
 /* Build the table over a vocabulary's own token ids (section 4.1: bytes are mapped to their initial token ids
  * by lookup; section 5.1 runs a pretrained tokenizer's vocabulary, whose ids are not "byte value" and
  * "256 + rank").  Same table, same encoding; only the numbering of the tokens differs:

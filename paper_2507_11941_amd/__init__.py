@@ -5,7 +5,7 @@ PyTorch is used for device memory and streams only; every step of the encode run
 There is no CPU fallback: if the library is missing or no GPU is present the calls raise.
 """
 from ._binding import (BpeError, Table, build_table, build_table_vocab, encode_batch, read_profile, lib_path, load_library,
-                       set_profiling, workspace_bytes, MAX_STRING_BYTES)
+                       set_profiling, table_image, workspace_bytes, MAX_STRING_BYTES)
 
 __all__ = ["BpeError", "Table", "build_table", "build_table_vocab", "encode_batch", "read_profile", "lib_path",
-           "load_library", "set_profiling", "workspace_bytes", "MAX_STRING_BYTES"]
+           "load_library", "set_profiling", "table_image", "workspace_bytes", "MAX_STRING_BYTES"]

@@ -41,6 +41,8 @@ def load_library():
     lib.bpe_build_table.restype = ctypes.c_int
     lib.bpe_build_table_vocab.argtypes = [vp, vp, vp, i32, ctypes.POINTER(vp), ctypes.POINTER(i32)]
     lib.bpe_build_table_vocab.restype = ctypes.c_int
+    lib.bpe_table_image.argtypes = [vp, i32, vp, ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.bpe_table_image.restype = ctypes.c_int64
     lib.bpe_free_table.argtypes = [vp]
     lib.bpe_free_table.restype = None
     lib.bpe_table_n_merges.argtypes = [vp]
@@ -97,6 +99,20 @@ def build_table(merges) -> Table:
     if code != 0:
         raise BpeError(code, "bpe_build_table", f"{lib.bpe_strerror(code).decode()} (row {bad.value})")
     return Table(handle.value, len(m))
+
+
+def table_image(merges):
+    """The host-memory image of the table (uint32 array) and log2 of its bucket count; needs no GPU."""
+    lib = load_library()
+    m = np.ascontiguousarray(np.asarray(merges, dtype=np.int32).reshape(-1, 2))
+    ptr = m.ctypes.data if len(m) else None
+    bad, log2 = ctypes.c_int32(-1), ctypes.c_int32(0)
+    n = lib.bpe_table_image(ptr, len(m), None, 0, ctypes.byref(log2), ctypes.byref(bad))
+    if n < 0:
+        raise BpeError(int(n), "bpe_table_image", f"{lib.bpe_strerror(int(n)).decode()} (row {bad.value})")
+    words = np.empty(n, dtype=np.uint32)
+    lib.bpe_table_image(ptr, len(m), words.ctypes.data, n, ctypes.byref(log2), ctypes.byref(bad))
+    return words, log2.value
 
 
 def build_table_vocab(byte_ids, merges, merged_ids) -> Table:

@@ -198,11 +198,9 @@ extern "C" {
 
 namespace {
 
-// merges: rows in the library's own numbering (byte b = b, row r creates 256 + r); id_map: null, or the
-// vocabulary id of each of the 256 + n_merges tokens, which the packing kernels then write instead.
-int build_table(const int32_t* merges, int32_t n_merges, const int32_t* id_map, bpe_table** out,
+// The table as it lies in device memory, built in host memory: [buckets | byte_word[256] | byte_pair[65536]].
+int build_image(const int32_t* merges, int32_t n_merges, std::vector<uint32_t>& host, int& log2_buckets_out,
                 int32_t* bad_row) {
-
   // operands must exist before the row that uses them
   for (int32_t r = 0; r < n_merges; ++r) {
     const int32_t a = merges[2 * r], b = merges[2 * r + 1];
@@ -212,7 +210,6 @@ int build_table(const int32_t* merges, int32_t n_merges, const int32_t* id_map, 
     }
   }
 
-  std::vector<uint32_t> host;
   std::vector<int32_t> first_left, first_right;                // first row that uses a token as left / right
   try {
     first_left.assign((size_t)n_merges + 256, -1);
@@ -300,12 +297,23 @@ int build_table(const int32_t* merges, int32_t n_merges, const int32_t* id_map, 
   uint32_t* byte_word = host.data() + n_words;
   for (uint32_t b = 0; b < 256; ++b)
     byte_word[b] = b | (first_left[b] >= 0 ? kTokCanLeft : 0u) | (first_right[b] >= 0 ? kTokCanRight : 0u);
+  log2_buckets_out = log2_buckets;
+  return BPE_OK;
+}
 
+// merges: rows in the library's own numbering (byte b = b, row r creates 256 + r); id_map: null, or the
+// vocabulary id of each of the 256 + n_merges tokens, which the packing kernels then write instead.
+int build_table(const int32_t* merges, int32_t n_merges, const int32_t* id_map, bpe_table** out,
+                int32_t* bad_row) {
+  std::vector<uint32_t> host;
+  int log2_buckets = 0;
+  const int status = build_image(merges, n_merges, host, log2_buckets, bad_row);
+  if (status != BPE_OK) return status;
   bpe_table* t = new (std::nothrow) bpe_table();
   if (!t) return BPE_ENOMEM;
   t->n_merges = n_merges;
   t->log2_buckets = log2_buckets;
-  t->bucket_bytes = n_words * sizeof(uint32_t);
+  t->bucket_bytes = (host.size() - 256 - 65536) * sizeof(uint32_t);
   if (hipGetDevice(&t->device) != hipSuccess) { delete t; return BPE_EHIP; }
   const size_t map_words = id_map ? (size_t)n_merges + 256 : 0;
   hipError_t e = hipMalloc(&t->d_mem, (host.size() + map_words) * sizeof(uint32_t));
@@ -336,6 +344,20 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
   if (n_merges < 0 || (n_merges > 0 && !merges)) return BPE_EINVAL;
   if (n_merges > BPE_MAX_MERGES) return BPE_ETOOBIG;
   return build_table(merges, n_merges, nullptr, out, bad_row);
+}
+
+int64_t bpe_table_image(const int32_t* merges, int32_t n_merges, uint32_t* words, int64_t capacity,
+                        int32_t* log2_buckets, int32_t* bad_row) {
+  if (bad_row) *bad_row = -1;
+  if (n_merges < 0 || (n_merges > 0 && !merges) || capacity < 0 || (capacity > 0 && !words)) return BPE_EINVAL;
+  if (n_merges > BPE_MAX_MERGES) return BPE_ETOOBIG;
+  std::vector<uint32_t> host;
+  int log2 = 0;
+  const int status = build_image(merges, n_merges, host, log2, bad_row);
+  if (status != BPE_OK) return status;
+  if (log2_buckets) *log2_buckets = log2;
+  if ((int64_t)host.size() <= capacity) std::memcpy(words, host.data(), host.size() * sizeof(uint32_t));
+  return (int64_t)host.size();
 }
 
 int bpe_build_table_vocab(const int32_t* byte_ids, const int32_t* merges, const int32_t* merged_ids,
