@@ -118,3 +118,57 @@ def test_very_many_very_short_strings(bpe):
     for n_strings, length in ((65536, 1), (100000, 0), (50000, 3)):
         off = np.arange(n_strings + 1, dtype=np.int64) * length
         check(bpe, merges, text[: int(off[-1])], off, f"{n_strings} strings of {length}")
+
+
+def test_two_streams_and_graph_replay(bpe):
+    """bpe_encode_batch only enqueues: two calls on two streams with their own workspaces do not disturb each
+    other, and a call captured into a HIP graph gives the eager result on every replay, also after the input
+    buffer's contents have changed."""
+    import torch
+
+    merges = workloads.load_merges("32k")
+    table = bpe.build_table(merges)
+    orc = oracle.Table(merges)
+    dev = torch.device("cuda:0")
+    batches = [workloads.batch(2, batch_override=700), workloads.batch(3, batch_override=40)]
+    wants = [orc.encode_batch(d, o, tier=oracle.HEAP, nthreads=THREADS) for d, o in batches]
+    streams = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]
+    outs = []
+    for (data, off), stream in zip(batches, streams):
+        d, o = torch.from_numpy(data).to(dev), torch.from_numpy(off).to(dev)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                ids, out_off = bpe.encode_batch(table, d, o, int(np.diff(off).max()), stream=stream)
+        outs.append((ids, out_off))
+    torch.cuda.synchronize()
+    for (ids, out_off), (want_ids, want_off) in zip(outs, wants):
+        out_off = out_off.cpu().numpy()
+        assert_same_encoding(ids[: int(out_off[-1])].cpu().numpy(), out_off, want_ids, want_off, "two streams")
+
+    # graph capture of one call, replayed over changing inputs of the same shape
+    data, off = batches[0]
+    lens_max = int(np.diff(off).max())
+    d, o = torch.from_numpy(data).to(dev), torch.from_numpy(off).to(dev)
+    out_ids = torch.empty(len(data), dtype=torch.int32, device=dev)
+    out_off = torch.empty(len(off), dtype=torch.int64, device=dev)
+    ws = torch.empty(bpe.workspace_bytes(len(off) - 1, len(data), lens_max), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream(device=dev)
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        bpe.encode_batch(table, d, o, lens_max, out_ids, out_off, ws, stream=torch.cuda.current_stream(dev))
+    rng = np.random.default_rng(5)
+    for replay in range(4):
+        if replay:                                        # same offsets, other bytes
+            data = workloads.text(2, 900 + replay, len(data))
+            d.copy_(torch.from_numpy(data).to(dev))
+        out_ids.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want_ids, want_off = orc.encode_batch(data, off, tier=oracle.HEAP, nthreads=THREADS)
+        got_off = out_off.cpu().numpy()
+        assert_same_encoding(out_ids[: int(got_off[-1])].cpu().numpy(), got_off, want_ids, want_off,
+                             f"graph replay {replay}")
+    table.free()
