@@ -34,12 +34,15 @@ enum {
   BPE_ENOMEM = -4,    /* host or device allocation failed */
   BPE_EHIP = -5,      /* a HIP runtime call failed */
   BPE_ETOOBIG = -6,   /* more merges than the table format holds */
-  BPE_EDUPID = -7     /* bpe_build_table_vocab: two tokens of the vocabulary share an id */
+  BPE_EDUPID = -7,    /* bpe_build_table_vocab: two tokens of the vocabulary share an id */
+  BPE_ESPECIAL = -8   /* bpe_table_set_specials: two special tokens could overlap in a text, or are the same */
 };
 
 /* Largest string (bytes) bpe_encode_batch accepts, and largest number of merge rows a table holds. */
 #define BPE_MAX_STRING_BYTES 65536
 #define BPE_MAX_MERGES 1048318 /* ids stay below 2^20 - 1 */
+#define BPE_MAX_SPECIALS 64
+#define BPE_MAX_SPECIAL_BYTES 64
 
 /* Build the GPU-resident merge table (the map R of Algorithm 1: pair -> rank, O(1) lookup; section 4.3's
  * GPU hashmap).
@@ -77,6 +80,23 @@ int64_t bpe_table_image(const int32_t* merges, int32_t n_merges, uint32_t* words
  * bpe_encode_batch on such a table writes vocabulary ids to out_ids.  The arrays are copied. */
 int bpe_build_table_vocab(const int32_t* byte_ids, const int32_t* merges, const int32_t* merged_ids,
                           int32_t n_merges, bpe_table** out, int32_t* bad_row);
+
+/* Special tokens (section 4.1: special-character lookups identify BOS, EOS and the other reserved strings
+ * before any merging).  After this call bpe_encode_batch treats every occurrence of one of the given byte
+ * strings as a single token with the given id: the string is read left to right, where several specials match
+ * the longest is taken, reading goes on after it, and the stretches in between are encoded by Algorithm 1 on
+ * their own (no merge involves or crosses a special token).
+ *   text          HOST, uint8: the specials' byte strings back to back.
+ *   text_offsets  HOST, int32[n+1]: special i is text[text_offsets[i] .. text_offsets[i+1]), 1..64 bytes.
+ *   ids           HOST, int32[n], >= 0: written to out_ids as given (they are not looked up in a vocabulary).
+ *   n             0..BPE_MAX_SPECIALS; 0 removes the special tokens.
+ * The set must be such that two occurrences can never overlap in any text: no special may contain, from an
+ * offset > 0 on, another special or the beginning of one that runs past its end (BPE_ESPECIAL otherwise; the
+ * usual reserved strings, bracketed by characters that occur nowhere inside them, satisfy this).  A special may
+ * be the beginning of a longer one.  Set-up call: copies the arrays, allocates device memory, synchronous; the
+ * caller must not run it while an encode that uses the table is enqueued or running. */
+int bpe_table_set_specials(bpe_table* table, const uint8_t* text, const int32_t* text_offsets, const int32_t* ids,
+                           int32_t n);
 
 /* Release a table.  NULL is allowed.  The caller must have drained every stream that uses it. */
 void bpe_free_table(bpe_table* table);

@@ -41,6 +41,8 @@ def _load():
         lib.orc_table_new_vocab.restype = vp
         lib.orc_table_free.argtypes = [vp]
         lib.orc_table_free.restype = None
+        lib.orc_table_set_specials.argtypes = [vp, vp, vp, vp, i32]
+        lib.orc_table_set_specials.restype = None
         lib.orc_encode.argtypes = [vp, ci, vp, i64, vp, vp]
         lib.orc_encode.restype = i64
         lib.orc_encode_batch.argtypes = [vp, ci, vp, vp, i64, ci, vp, vp, vp]
@@ -80,6 +82,17 @@ class Table:
                 raise ValueError("byte_ids must have 256 entries and merged_ids one per row")
             self._h = _load().orc_table_new_vocab(self.byte_ids.ctypes.data, self.merges.ctypes.data,
                                                   self.merged_ids.ctypes.data, len(self.merges))
+
+    def set_specials(self, specials):
+        """specials: {bytes: id}.  Their occurrences (left to right, the longest where several match) become
+        one token each; the text between them is encoded on its own.  An empty dict removes them."""
+        items = [(bytes(k), int(v)) for k, v in dict(specials).items()]
+        text = np.frombuffer(b"".join(k for k, _ in items), dtype=np.uint8).copy()
+        off = np.zeros(len(items) + 1, dtype=np.int32)
+        np.cumsum([len(k) for k, _ in items], out=off[1:])
+        ids = np.array([v for _, v in items], dtype=np.int32)
+        _load().orc_table_set_specials(self._h, text.ctypes.data if len(text) else None, off.ctypes.data,
+                                       ids.ctypes.data if len(ids) else None, len(items))
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

@@ -67,6 +67,11 @@ struct Table {
   std::vector<int32_t> merged_id;                  // [rows]
   std::unordered_map<int32_t, int32_t> byte_of_id, row_of_id;   // inverse, for decode
 
+  // Special tokens (section 4.1: special-character lookups identify BOS / EOS and the other reserved strings
+  // before any merging): byte strings that become one token each.
+  std::vector<std::string> special_text;
+  std::vector<int32_t> special_id;
+
   std::vector<int32_t> initial(const uint8_t* s, int64_t n) const {   // "split S into a list of bytes"
     std::vector<int32_t> T((size_t)n);
     for (int64_t i = 0; i < n; ++i) T[(size_t)i] = byte_id[s[i]];
@@ -199,6 +204,8 @@ std::vector<int32_t> encode_heap(const Table& t, const uint8_t* s, int64_t n) {
 }
 
 void decode_id(const Table& t, int32_t id, std::string& out) {
+  for (size_t i = 0; i < t.special_id.size(); ++i)
+    if (t.special_id[i] == id) { out += t.special_text[i]; return; }
   auto b = t.byte_of_id.find(id);
   if (b != t.byte_of_id.end()) { out.push_back((char)b->second); return; }
   const auto& row = t.rows[(size_t)t.row_of_id.at(id)];
@@ -206,7 +213,40 @@ void decode_id(const Table& t, int32_t id, std::string& out) {
   decode_id(t, row.second, out);
 }
 
+std::vector<int32_t> encode_plain(const Table& t, int tier, const uint8_t* s, int64_t n, PassStats* st);
+
+// With special tokens: read the string left to right; where one or more specials match, the longest one
+// becomes a single token with its id and reading goes on after it; the stretches in between are encoded by
+// Algorithm 1 on their own (no merge involves a special token or crosses one).
 std::vector<int32_t> encode_tier(const Table& t, int tier, const uint8_t* s, int64_t n, PassStats* st) {
+  if (t.special_text.empty()) return encode_plain(t, tier, s, n, st);
+  std::vector<int32_t> out;
+  int64_t stretch = 0, p = 0;
+  auto flush = [&](int64_t end) {
+    if (end > stretch) {
+      std::vector<int32_t> ids = encode_plain(t, tier, s + stretch, end - stretch, st);
+      out.insert(out.end(), ids.begin(), ids.end());
+    }
+  };
+  while (p < n) {
+    int best = -1;
+    for (size_t i = 0; i < t.special_text.size(); ++i) {
+      const std::string& w = t.special_text[i];
+      if ((int64_t)w.size() <= n - p && std::memcmp(w.data(), s + p, w.size()) == 0 &&
+          (best < 0 || w.size() > t.special_text[(size_t)best].size()))
+        best = (int)i;
+    }
+    if (best < 0) { ++p; continue; }
+    flush(p);
+    out.push_back(t.special_id[(size_t)best]);
+    p += (int64_t)t.special_text[(size_t)best].size();
+    stretch = p;
+  }
+  flush(n);
+  return out;
+}
+
+std::vector<int32_t> encode_plain(const Table& t, int tier, const uint8_t* s, int64_t n, PassStats* st) {
   switch (tier) {
     case 0: return encode_bruteforce(t, s, n);
     case 1: return encode_textbook(t, s, n);
@@ -388,6 +428,17 @@ void* orc_table_new(const int32_t* merges, int32_t n_merges) {
 }
 
 void orc_table_free(void* h) { delete (Table*)h; }
+
+// Special tokens: n byte strings (text[offsets[i] .. offsets[i+1])) with their ids; n = 0 removes them.
+void orc_table_set_specials(void* h, const uint8_t* text, const int32_t* offsets, const int32_t* ids, int32_t n) {
+  Table* t = (Table*)h;
+  t->special_text.clear();
+  t->special_id.clear();
+  for (int32_t i = 0; i < n; ++i) {
+    t->special_text.emplace_back((const char*)text + offsets[i], (size_t)(offsets[i + 1] - offsets[i]));
+    t->special_id.push_back(ids[i]);
+  }
+}
 
 // Encode one string with encoder `tier` (0 brute force, 1 textbook, 2 passes, 3 heap).
 // out must hold n ids.  stats (may be null) = {passes, visits, merges}, filled by tier 2 only.

@@ -43,6 +43,8 @@ def load_library():
     lib.bpe_build_table_vocab.restype = ctypes.c_int
     lib.bpe_table_image.argtypes = [vp, i32, vp, ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.bpe_table_image.restype = ctypes.c_int64
+    lib.bpe_table_set_specials.argtypes = [vp, vp, vp, vp, i32]
+    lib.bpe_table_set_specials.restype = ctypes.c_int
     lib.bpe_free_table.argtypes = [vp]
     lib.bpe_free_table.restype = None
     lib.bpe_table_n_merges.argtypes = [vp]
@@ -76,6 +78,18 @@ class Table:
     @property
     def handle(self) -> int:
         return self._h
+
+    def set_specials(self, specials):
+        """specials: {bytes: id}; every occurrence of one of the byte strings becomes one token with that id
+        (bpe_table_set_specials).  An empty dict removes them."""
+        items = [(bytes(k), int(v)) for k, v in dict(specials).items()]
+        text = np.frombuffer(b"".join(k for k, _ in items), dtype=np.uint8).copy()
+        off = np.zeros(len(items) + 1, dtype=np.int32)
+        np.cumsum([len(k) for k, _ in items], out=off[1:])
+        ids = np.array([v for _, v in items], dtype=np.int32)
+        _check(load_library().bpe_table_set_specials(self._h, text.ctypes.data if len(text) else None,
+                                                     off.ctypes.data, ids.ctypes.data if len(ids) else None,
+                                                     len(items)), "bpe_table_set_specials")
 
     def free(self):
         if self._h:

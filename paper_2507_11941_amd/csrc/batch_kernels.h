@@ -224,7 +224,8 @@ __global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offset
 __global__ __launch_bounds__(256) void cut_search_kernel(const uint8_t* bytes, const int64_t* offsets,
                                                          const uint32_t* byte_pair, int piece_target,
                                                          int max_string, const Control* c, const int32_t* slot_base,
-                                                         const int32_t* slot_string, int64_t* piece_begin) {
+                                                         const int32_t* slot_string, int64_t* piece_begin,
+                                                         const uint8_t* cover) {
   const uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (g >= c->n_slots) return;
@@ -243,8 +244,13 @@ __global__ __launch_bounds__(256) void cut_search_kernel(const uint8_t* bytes, c
     const int64_t t = begin + (int64_t)i * piece_target;
     const int64_t q0 = t - 2 * lane;
     const uint32_t a = bytes[q0 - 2], b = bytes[q0 - 1], cc = bytes[q0];
-    const bool cut0 = byte_pair[(b << 8) | cc] == kCut;      // before q0
-    const bool cut1 = byte_pair[(a << 8) | b] == kCut;       // before q0 - 1
+    bool cut0 = byte_pair[(b << 8) | cc] == kCut;            // before q0
+    bool cut1 = byte_pair[(a << 8) | b] == kCut;             // before q0 - 1
+    if (cover) {                                             // special tokens: their ends are cuts, their inside is not
+      const uint32_t ma = cover[q0 - 2], mb = cover[q0 - 1], mc = cover[q0];
+      cut0 = (cut0 || mb != 0 || mc != 0) && mc != kCoverRest;
+      cut1 = (cut1 || ma != 0 || mb != 0) && mb != kCoverRest;
+    }
     const uint64_t m0 = __ballot(cut0), m1 = __ballot(cut1);
     const uint64_t any = m0 | m1;
     if (any) {
@@ -397,6 +403,52 @@ __global__ __launch_bounds__(1024) void slot_offsets_kernel(const int32_t* count
     __syncthreads();
     if (tid == 1023) carry_s = before + v;
     __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Special tokens (section 4.1: special-character lookups before any merging).  The set is small (at most 64
+// strings of at most 64 bytes) and, by construction of the set, occurrences cannot overlap, so every byte
+// position can decide on its own whether an occurrence starts there: the longest special that matches.
+
+constexpr int kMaxSpecials = 64, kMaxSpecialBytes = 64;
+
+struct SpecialSet {
+  uint32_t first_byte[8];                              // bit b: some special starts with byte b
+  int32_t n;
+  int32_t len[kMaxSpecials];
+  uint8_t text[kMaxSpecials][kMaxSpecialBytes];
+};
+
+__global__ __launch_bounds__(256) void cover_clear_kernel(uint8_t* cover, int64_t total_bytes) {
+  const int64_t words = (total_bytes + 3) / 4;         // the buffer is padded to whole words
+  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < words; i += gridDim.x * 256ll) ((uint32_t*)cover)[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void special_mark_kernel(const uint8_t* bytes, const int64_t* offsets, int batch,
+                                                           int64_t total_bytes, const SpecialSet* set,
+                                                           uint8_t* cover) {
+  for (int64_t p = blockIdx.x * 256ll + threadIdx.x; p < total_bytes; p += gridDim.x * 256ll) {
+    const uint32_t b = bytes[p];
+    if (!((set->first_byte[b >> 5] >> (b & 31)) & 1u)) continue;
+    int lo = 0, hi = batch - 1;                        // the string that holds p: last s with offsets[s] <= p
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (offsets[mid] <= p) lo = mid; else hi = mid - 1;
+    }
+    const int64_t room = offsets[lo + 1] - p;          // bytes from p to the end of its string
+    int best = -1, best_len = 0;
+    for (int i = 0; i < set->n; ++i) {
+      const int len = set->len[i];
+      if (len <= best_len || len > room || set->text[i][0] != b) continue;
+      int j = 1;
+      while (j < len && bytes[p + j] == set->text[i][j]) ++j;
+      if (j == len) { best = i; best_len = len; }
+    }
+    if (best >= 0) {
+      cover[p] = (uint8_t)(kCoverFirst | (uint32_t)best);
+      for (int j = 1; j < best_len; ++j) cover[p + j] = (uint8_t)kCoverRest;
+    }
   }
 }
 

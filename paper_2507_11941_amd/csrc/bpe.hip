@@ -26,7 +26,11 @@ struct bpe_table {
   void* d_mem = nullptr;          // buckets, then the 256 byte token words, then the 256 x 256 byte-pair values,
                                   // then (tables over a vocabulary only) the id of every token, int32[256 + rows]
   size_t bucket_bytes = 0;
-  const int32_t* d_id_map = nullptr;   // inside d_mem; null: byte b is id b, row r creates id 256 + r
+  const int32_t* d_id_map = nullptr;   // null: byte b is id b, row r creates id 256 + r.  Inside d_mem, or
+                                       // d_special_mem once special tokens are set
+  std::vector<int32_t> id_map_host;    // the vocabulary ids of the 256 + rows tokens (empty: the default)
+  void* d_special_mem = nullptr;       // SpecialSet, then the id map extended by the specials' ids
+  const SpecialSet* d_specials = nullptr;
 };
 
 namespace {
@@ -147,7 +151,7 @@ struct WorkspaceLayout {
   bool split;                        // strings are cut into pieces
   int64_t max_slots;                 // upper bound on the number of work items (strings or piece slots)
   int n_tiles;                       // scan tiles over the slots
-  size_t control, list, counts, tmp_ids, staged;
+  size_t control, list, counts, tmp_ids, cover, staged;
   size_t slot_base, slot_string, piece_begin, piece_len, slot_out, tile_sum;   // split only
   size_t total;
 };
@@ -162,6 +166,7 @@ WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) 
   w.list = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.counts = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.tmp_ids = at; at += align_up((size_t)total_bytes * sizeof(int32_t));
+  w.cover = at; at += align_up((size_t)total_bytes + 4);      // special-token marks, one per byte
   w.slot_base = w.slot_string = w.piece_begin = w.piece_len = w.slot_out = w.tile_sum = 0;
   if (w.split) {
     w.slot_base = at; at += align_up(((size_t)batch + 1) * sizeof(int32_t));
@@ -323,6 +328,11 @@ int build_table(const int32_t* merges, int32_t n_merges, const int32_t* id_map, 
     int32_t* d_map = (int32_t*)((uint32_t*)t->d_mem + host.size());
     ok = hipMemcpy(d_map, id_map, map_words * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     t->d_id_map = d_map;
+    try {
+      t->id_map_host.assign(id_map, id_map + map_words);
+    } catch (const std::bad_alloc&) {
+      ok = false;
+    }
   }
   if (!ok) {
     (void)hipFree(t->d_mem);
@@ -401,8 +411,73 @@ int bpe_build_table_vocab(const int32_t* byte_ids, const int32_t* merges, const 
   return build_table(own.data(), n_merges, id_map.data(), out, bad_row);
 }
 
+int bpe_table_set_specials(bpe_table* table, const uint8_t* text, const int32_t* text_offsets, const int32_t* ids,
+                           int32_t n) {
+  if (!table || n < 0 || n > BPE_MAX_SPECIALS || (n > 0 && (!text || !text_offsets || !ids))) return BPE_EINVAL;
+  if (256 + (int64_t)table->n_merges + n > 0xFFFFE) return BPE_ETOOBIG;      // token numbers stay below 2^20 - 1
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return BPE_EHIP;
+  if (device != table->device) return BPE_EINVAL;
+  void* fresh = nullptr;
+  const SpecialSet* d_set = nullptr;
+  const int32_t* d_map = nullptr;
+  if (n > 0) {
+    SpecialSet set;
+    std::memset(&set, 0, sizeof(set));
+    set.n = n;
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t len = text_offsets[i + 1] - text_offsets[i];
+      if (len < 1 || len > BPE_MAX_SPECIAL_BYTES || ids[i] < 0) return BPE_EINVAL;
+      set.len[i] = len;
+      std::memcpy(set.text[i], text + text_offsets[i], (size_t)len);
+      set.first_byte[set.text[i][0] >> 5] |= 1u << (set.text[i][0] & 31);
+    }
+    // Occurrences must not be able to overlap: no special may hold, from some offset > 0 on, the beginning
+    // of a special (be it all of that special, or as much of it as fits before the first one ends).
+    for (int32_t a = 0; a < n; ++a)
+      for (int32_t b = 0; b < n; ++b)
+        for (int32_t o = 1; o < set.len[a]; ++o) {
+          const int32_t m = std::min(set.len[b], set.len[a] - o);
+          if (std::memcmp(set.text[a] + o, set.text[b], (size_t)m) == 0) return BPE_ESPECIAL;
+        }
+    for (int32_t a = 0; a < n; ++a)                       // two specials with the same text
+      for (int32_t b = a + 1; b < n; ++b)
+        if (set.len[a] == set.len[b] && std::memcmp(set.text[a], set.text[b], (size_t)set.len[a]) == 0)
+          return BPE_ESPECIAL;
+    // ids of all tokens: the table's (default or vocabulary), then the specials'
+    const size_t n_tokens = 256 + (size_t)table->n_merges;
+    std::vector<int32_t> map;
+    try {
+      map.resize(n_tokens + (size_t)n);
+    } catch (const std::bad_alloc&) {
+      return BPE_ENOMEM;
+    }
+    for (size_t t = 0; t < n_tokens; ++t) map[t] = table->id_map_host.empty() ? (int32_t)t : table->id_map_host[t];
+    for (int32_t i = 0; i < n; ++i) map[n_tokens + (size_t)i] = ids[i];
+    const size_t set_bytes = (sizeof(SpecialSet) + 255) & ~(size_t)255;
+    hipError_t e = hipMalloc(&fresh, set_bytes + map.size() * sizeof(int32_t));
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? BPE_ENOMEM : BPE_EHIP;
+    if (hipMemcpy(fresh, &set, sizeof(set), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy((char*)fresh + set_bytes, map.data(), map.size() * sizeof(int32_t), hipMemcpyHostToDevice) !=
+            hipSuccess) {
+      (void)hipFree(fresh);
+      return BPE_EHIP;
+    }
+    d_set = (const SpecialSet*)fresh;
+    d_map = (const int32_t*)((char*)fresh + set_bytes);
+  } else if (!table->id_map_host.empty()) {
+    d_map = (const int32_t*)((const uint32_t*)table->d_mem + table->bucket_bytes / sizeof(uint32_t) + 256 + 65536);
+  }
+  if (table->d_special_mem) (void)hipFree(table->d_special_mem);
+  table->d_special_mem = fresh;
+  table->d_specials = d_set;
+  table->d_id_map = d_map;
+  return BPE_OK;
+}
+
 void bpe_free_table(bpe_table* table) {
   if (!table) return;
+  if (table->d_special_mem) (void)hipFree(table->d_special_mem);
   if (table->d_mem) (void)hipFree(table->d_mem);
   delete table;
 }
@@ -442,6 +517,15 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   plan.n_tiers = n_tiers_for(max_len);
   for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_tier_cap[t];
 
+  const uint8_t* cover = nullptr;                        // special tokens: mark their occurrences first
+  if (table->d_specials && batch > 0 && total_bytes > 0) {
+    uint8_t* marks = (uint8_t*)(ws + w.cover);
+    const int grid = (int)std::min<int64_t>((total_bytes + 255) / 256, 16384);
+    hipLaunchKernelGGL(cover_clear_kernel, dim3(grid), dim3(256), 0, stream, marks, total_bytes);
+    hipLaunchKernelGGL(special_mark_kernel, dim3(grid), dim3(256), 0, stream, bytes, offsets, batch, total_bytes,
+                       table->d_specials, marks);
+    cover = marks;
+  }
   const int64_t* piece_begin = nullptr;
   const int32_t* piece_len = nullptr;
   const int32_t* slot_base = nullptr;
@@ -465,7 +549,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
       hipLaunchKernelGGL(slot_layout_kernel, dim3((unsigned)((batch + 1023) / 1024)), dim3(1024), 0, stream, offsets, batch, kPieceTarget,
                          BPE_MAX_STRING_BYTES, ctrl, sb, ss);
       hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 3) / 4)), dim3(256), 0, stream, bytes,
-                         offsets, byte_pair, kPieceTarget, BPE_MAX_STRING_BYTES, ctrl, sb, ss, pb);
+                         offsets, byte_pair, kPieceTarget, BPE_MAX_STRING_BYTES, ctrl, sb, ss, pb, cover);
       hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
                          pb, pl, counts);
       hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
@@ -493,6 +577,8 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     p.tmp_ids = tmp_ids;
     p.counts = counts;
     p.direct_count = (uint32_t)batch;
+    p.cover = cover;
+    p.special_base = 256u + (uint32_t)table->n_merges;
     // Warming L2 pays once the batch probes the table more often than it has lines: ~1 probe per input byte.
     const size_t table_bytes = table->bucket_bytes + (256 + 65536) * sizeof(uint32_t);
     p.prefetch_lines = (size_t)total_bytes >= table_bytes / 4 ? (uint32_t)(table_bytes / 128) : 0u;
@@ -594,6 +680,7 @@ const char* bpe_strerror(int code) {
     case BPE_EHIP: return "HIP runtime call failed";
     case BPE_ETOOBIG: return "too many merge rows for the table format";
     case BPE_EDUPID: return "two tokens of the vocabulary share an id";
+    case BPE_ESPECIAL: return "occurrences of the special tokens could overlap";
     default: return "unknown error";
   }
 }

@@ -62,7 +62,19 @@ struct EncodeParams {
   uint32_t prefetch_lines;    // 128-byte lines of table memory to pull into L2 at kernel start (0 = none)
   uint32_t direct_count;      // when `list` is null: items are the strings 0..direct_count-1, one per workgroup
   int tier;
+  const uint8_t* cover;       // null, or one mark per input byte: where the special tokens lie (see kCover*)
+  uint32_t special_base;      // token number of special 0 (256 + rows)
 };
+
+// What the load phases make of them: "byte codes" above the byte values.  Any code >= 0x100 is no byte, so
+// the pair on either side of it counts as a cut and is in no table.
+constexpr uint32_t kCodeNone = 0x100u;      // outside the string
+constexpr uint32_t kCodeRest = 0x200u;      // inside a special occurrence: no token here
+constexpr uint32_t kCodeSpecial = 0x400u;   // | index: the occurrence's single token
+
+__device__ inline uint32_t cover_code(uint32_t byte, uint32_t mark) {
+  return mark == 0 ? byte : ((mark & kCoverFirst) ? (kCodeSpecial | (mark & kCoverIndex)) : kCodeRest);
+}
 
 // ---------------------------------------------------------------------------------------------------
 // wave64 primitives
@@ -393,10 +405,18 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         const int i = base + k0 + j;
         b[j] = (k0 + j <= c0 && i < n) ? src[i] : 0x100u;   // 0x100: no such byte
       }
+      if (p.cover) {                                   // uniform: special tokens are configured
+        const uint8_t* mark = p.cover + begin;
+#pragma unroll
+        for (int j = 0; j <= kChunk; ++j) {
+          const int i = base + k0 + j;
+          if (k0 + j <= c0 && i < n) b[j] = cover_code(b[j], mark[i]);
+        }
+      }
       uint32_t v[kChunk];
 #pragma unroll
       for (int j = 0; j < kChunk; ++j)
-        v[j] = (k0 + j < c0 && b[j + 1] < 0x100u) ? tab.byte_pair[(b[j] << 8) | b[j + 1]] : kNoRank;
+        v[j] = (k0 + j < c0 && b[j] < 0x100u && b[j + 1] < 0x100u) ? tab.byte_pair[(b[j] << 8) | b[j + 1]] : kNoRank;
 #pragma unroll
       for (int j = 0; j < kChunk; ++j) {
         const int k = k0 + j;
@@ -407,8 +427,9 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
           if (LIMITS) L[k * W + tid] = lim;
           llim = min(llim, lim);
           if (k < c0) {
-            const uint32_t w = sh.byte_word[b[j]];
+            const uint32_t w = (b[j] & kCodeSpecial) ? p.special_base + (b[j] & kCoverIndex) : sh.byte_word[b[j] & 0xFFu];
             T[k * W + tid] = w;
+            if (b[j] & kCodeRest) live &= ~bit_at<mask_t>(k);
             if (k == 0) { ftok = w; firstv = v[j]; }
             if (k == c0 - 1) {
               lastv = v[j];
@@ -417,6 +438,11 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
           }
         }
       }
+    }
+    if (p.cover) {                                     // positions may be dead from the start: look again
+      ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
+      firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
+      lastv = live ? V[top_bit<mask_t>(live) * W + tid] : kNoRank;
     }
   }
 

@@ -99,6 +99,14 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       const int i = base - 1 + j;
       b[j] = (j <= c0 + 1 && c0 > 0 && i >= 0 && i < n) ? src[i] : 0x100u;
     }
+    if (p.cover) {                                     // uniform: special tokens are configured
+      const uint8_t* mark = p.cover + begin;
+#pragma unroll
+      for (int j = 0; j < D + 2; ++j) {
+        const int i = base - 1 + j;
+        if (j <= c0 + 1 && c0 > 0 && i >= 0 && i < n) b[j] = cover_code(b[j], mark[i]);
+      }
+    }
     uint32_t raw[D + 1];                               // raw[j]: table entry of the pair (b[j], b[j+1])
 #pragma unroll
     for (int j = 0; j < D + 1; ++j)
@@ -116,8 +124,10 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         V[k * W + tid] = v;
         if (LIMITS) L[k * W + tid] = limit20_of(v);
         if (k < c0) {
-          const uint32_t w = sh.byte_word[b[k + 1]];
+          const uint32_t code = b[k + 1];
+          const uint32_t w = (code & kCodeSpecial) ? p.special_base + (code & kCoverIndex) : sh.byte_word[code & 0xFFu];
           T[k * W + tid] = w;
+          if (code & kCodeRest) live &= ~bit_at<mask_t>(k);
           if (k == 0) { ftok = w; firstv = v; }
           if (k == c0 - 1) {
             lastv = v;
@@ -125,6 +135,12 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           }
         }
       }
+    }
+    if (p.cover) {                                     // positions may be dead from the start
+      cuts &= live;                                    // a segment starts at a token
+      ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
+      firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
+      lastv = live ? V[top_bit<mask_t>(live) * W + tid] : kNoRank;
     }
   }
   const uint64_t cut_first = __ballot((cuts & 1u) != 0);   // lanes whose column starts a segment (for good)

@@ -61,6 +61,10 @@ constexpr uint32_t kTokCanLeft = 1u << 30;
 constexpr uint32_t kTokCanRight = 1u << 31;
 constexpr uint32_t kTokNone = 0xFFFFFFFFu;    // "no token" marker (id field all ones is never a valid id)
 
+// Marks of the special-token pass (section 4.1's special-character lookup), one per input byte: 0 for ordinary
+// text, kCoverFirst | index on the first byte of an occurrence of special `index`, kCoverRest on its other bytes.
+constexpr uint32_t kCoverRest = 0x40u, kCoverFirst = 0x80u, kCoverIndex = 0x3Fu;
+
 struct Placement {
   uint32_t bucket;
   uint32_t fingerprint;

@@ -180,3 +180,70 @@ def test_random_vocabularies(bpe):
         want_ids, want_off = orc.encode_batch(data, off, tier=oracle.TEXTBOOK, nthreads=8)
         assert_same_encoding(ids, out_off, want_ids, want_off, f"vocabulary trial {trial}")
         table.free()
+
+
+def parse_specials(spec):
+    return {k.encode(): int(v) for k, v in (item.split("=") for item in spec.split(";"))}
+
+
+def test_hand_worked_special_examples(bpe):
+    by_table = {}
+    for row in read_golden("hand_worked_specials.txt"):
+        by_table.setdefault((row[0], row[1]), []).append((row[2].encode(), parse_ids(row[3])))
+    for (spec, specials), cases in by_table.items():
+        table = bpe.build_table(parse_rows(spec))
+        table.set_specials(parse_specials(specials))
+        ids, out_off = gpu_encode(table, *to_batch([c[0] for c in cases]))
+        for i, (text, want) in enumerate(cases):
+            assert ids[out_off[i]:out_off[i + 1]].tolist() == want, (spec, specials, text)
+        table.free()
+
+
+def test_special_sets_that_could_overlap_are_rejected(bpe):
+    table = bpe.build_table([(97, 98)])
+    for bad in ({b"aa": 1}, {b"<a>": 1, b"a": 2}, {b"<a>": 1, b"a><": 2}, {b"ab": 1, b"bc": 2}, {b"": 1},
+                {b"x" * 65: 1}, {b"<a>": -4}):
+        with pytest.raises(bpe.BpeError):
+            table.set_specials(bad)
+    table.set_specials({b"<a>": 1, b"<a>b": 2, b"[x]": 3})      # a special may begin a longer one
+    ids, _ = gpu_encode(table, *to_batch([b"ab<a>b[x]<a>"]))
+    assert ids.tolist() == [256, 2, 3, 1]
+    table.set_specials({})
+    ids, _ = gpu_encode(table, *to_batch([b"ab<a>"]))
+    assert ids.tolist() == [256, 60, 97, 62]
+    table.free()
+
+
+def test_random_texts_with_special_tokens(bpe):
+    """Specials sprinkled over random strings of every kernel variant's size, default and vocabulary ids."""
+    rng = random.Random(99)
+    specials = {b"<|endoftext|>": 70001, b"<|endoftext|>2": 70002, b"[SEP]": 70003, b"\x00": 70004,
+                b"<" + b"q" * 62 + b">": 70005}
+    for trial in range(6):
+        alphabet = [ord(c) for c in "ab|<>e "] + rng.sample(range(128, 256), 2)
+        rows = random_monotone_table(rng, rng.randint(5, 200), alphabet)
+        if trial % 2:
+            phi = np.array(rng.sample(range(60000), 256 + len(rows)), dtype=np.int32)
+            named = [(int(phi[a]), int(phi[b])) for a, b in rows]
+            orc = oracle.Table(named, phi[:256], phi[256:])
+            table = bpe.build_table_vocab(phi[:256], named, phi[256:])
+        else:
+            orc = oracle.Table(rows)
+            table = bpe.build_table(rows)
+        orc.set_specials(specials)
+        table.set_specials(specials)
+        strings = []
+        for n in (0, 1, 13, 14, 64, 200, 1000, 1024, 1500, 5000, 20000, 65536):
+            s = bytearray()
+            while len(s) < n:
+                if rng.random() < 0.15:
+                    s += rng.choice(list(specials))
+                else:
+                    s += bytes(rng.choice(alphabet) for _ in range(rng.choice((1, 3, 20, 150))))
+            strings.append(bytes(s[:n]))
+        strings += list(specials) + [b"".join(specials) * 3]
+        data, off = to_batch(strings)
+        ids, out_off = gpu_encode(table, data, off)
+        want_ids, want_off = orc.encode_batch(data, off, tier=oracle.HEAP, nthreads=8)
+        assert_same_encoding(ids, out_off, want_ids, want_off, f"specials trial {trial}")
+        table.free()
