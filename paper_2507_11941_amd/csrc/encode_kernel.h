@@ -220,13 +220,14 @@ __device__ inline void probe_start(const DeviceTable& t, uint32_t xw, uint32_t y
 }
 
 __device__ inline uint32_t probe_finish(const DeviceTable& t, const ProbeInFlight& f) {
-  if (!f.live) return kNoRank;
   const uint32_t tag = slot_tag(f.pl.fingerprint, 0);
-  if (f.x.y == tag) return f.x.x;
-  if (f.x.w == tag) return f.x.z;
-  if (f.y.y == tag) return f.y.x;
-  if (f.y.w == tag) return f.y.z;
-  if (f.y.w == 0xFFFFFFFFu) return kNoRank;
+  uint32_t found = kNoRank;                            // at most one slot matches: selects, not branches
+  found = f.x.y == tag ? f.x.x : found;
+  found = f.x.w == tag ? f.x.z : found;
+  found = f.y.y == tag ? f.y.x : found;
+  found = f.y.w == tag ? f.y.z : found;
+  if (!f.live) return kNoRank;
+  if (found != kNoRank || f.y.w == 0xFFFFFFFFu) return found;
   for (uint32_t step = 1; step <= kMaxDisplacement; ++step) {   // home bucket full: the key may be displaced
     const uint4* p = t.buckets + 2 * (size_t)((f.pl.bucket + step) & t.bucket_mask);
     const uint4 x = p[0], y = p[1];

@@ -30,10 +30,14 @@ constexpr uint32_t kAll20 = 0xFFFFEu;       // horizon above every rank (ranks s
 constexpr uint32_t kInf31 = 0x7FFFFFFFu;    // identity of the cross-wave segmented minimum
 constexpr uint32_t kReset31 = 0x80000000u;  // cross-wave element flag: a cut lies inside this span
 
+// (Straight-line on purpose: it runs once per position at load and once per look-up.)
 __device__ inline uint32_t limit20_of(uint32_t value) {
-  if (value == kNoRank) return kInf20;
-  const uint32_t lim = limit_of(value);
-  return lim >= kAll20 ? kAll20 : lim;
+  const uint32_t code = (value >> kHorizonShift) & 0xFFu;
+  const uint32_t e = code >> 4, m = code & 15u;
+  const uint32_t span = e ? ((16u | m) << (e - 1u)) : m;                  // horizon_decode(code)
+  uint32_t lim = min((value >> kRankShift) + 1u + span, kAll20);
+  lim = code == 255u ? kAll20 : lim;                                     // the token is never an operand
+  return value == kNoRank ? kInf20 : lim;
 }
 
 // Segmented minimum: apply(left, right) = right if a cut lies inside right, else the minimum of the two with
@@ -123,17 +127,17 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         }
         V[k * W + tid] = v;
         if (LIMITS) L[k * W + tid] = limit20_of(v);
-        if (k < c0) {
-          const uint32_t code = b[k + 1];
-          const uint32_t w = (code & kCodeSpecial) ? p.special_base + (code & kCoverIndex) : sh.byte_word[code & 0xFFu];
-          T[k * W + tid] = w;
-          if (code & kCodeRest) live &= ~bit_at<mask_t>(k);
-          if (k == 0) { ftok = w; firstv = v; }
-          if (k == c0 - 1) {
-            lastv = v;
-            if (b[k + 2] < 0x100u) succ_tok = sh.byte_word[b[k + 2]];
-          }
-        }
+        // (no lane-dependent branches here: positions from c0 on just get a token word nobody reads)
+        const uint32_t code = b[k + 1];
+        const uint32_t plain = sh.byte_word[code & 0xFFu];
+        const uint32_t w = (code & kCodeSpecial) ? p.special_base + (code & kCoverIndex) : plain;
+        T[k * W + tid] = w;
+        live &= (code & kCodeRest) ? ~bit_at<mask_t>(k) : ~(mask_t)0;
+        if (k == 0) { ftok = c0 > 0 ? w : ftok; firstv = c0 > 0 ? v : firstv; }
+        const bool last = k == c0 - 1;
+        lastv = last ? v : lastv;
+        const uint32_t after = sh.byte_word[b[k + 2] & 0xFFu];
+        succ_tok = (last && b[k + 2] < 0x100u) ? after : succ_tok;
       }
     }
     if (p.cover) {                                     // positions may be dead from the start
@@ -189,7 +193,10 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       if (g < d) {
 #pragma unroll
         for (int k = g; k < g + kGroup; ++k) {
-          if (!LIMITS) e[k] = limit20_of(v[k]);
+          if (!LIMITS) {                               // decoded on the fly; most positions hold no pair
+            e[k] = kInf20;
+            if (__ballot(v[k] != kNoRank)) e[k] = limit20_of(v[k]);
+          }
           const uint32_t at_cut = (uint32_t)__builtin_amdgcn_sbfe((int)cuts, k, 1);   // all ones at a cut
           run = min(run | at_cut, e[k]);               // a cut restarts the minimum
           f[k] = run;
