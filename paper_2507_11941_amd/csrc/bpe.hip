@@ -49,13 +49,13 @@ struct Variant {
   int max_grid = 0;               // resident workgroups on the whole device (filled on first use)
 };
 
-template <int NW, int D, bool ST, bool LIM, bool SEG>
+template <int NW, int D, bool ST, bool LIM, bool SEG, bool SPC>
 void launch_variant(const EncodeParams& p, int grid, hipStream_t stream) {
   constexpr size_t lds = encode_lds_bytes<NW, D, ST, LIM>();
-  encode_kernel<NW, D, ST, LIM, SEG><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
+  encode_kernel<NW, D, ST, LIM, SEG, SPC><<<dim3(grid), dim3(NW * 64), lds, stream>>>(p);
 }
 
-template <int NW, int D, bool ST, bool LIM, bool SEG>
+template <int NW, int D, bool ST, bool LIM, bool SEG, bool SPC>
 Variant make_variant() {
   Variant v;
   v.waves = NW;
@@ -64,19 +64,22 @@ Variant make_variant() {
   v.limits = LIM;
   v.capacity = 64 * NW * D;
   v.lds = encode_lds_bytes<NW, D, ST, LIM>();
-  v.fn = (const void*)&encode_kernel<NW, D, ST, LIM, SEG>;
-  v.launch = &launch_variant<NW, D, ST, LIM, SEG>;
+  v.fn = (const void*)&encode_kernel<NW, D, ST, LIM, SEG, SPC>;
+  v.launch = &launch_variant<NW, D, ST, LIM, SEG, SPC>;
   return v;
 }
 
 // Default plan: <= 1 KiB one wave, <= 4 KiB four waves, <= 16 KiB sixteen waves (all LDS-resident),
-// <= 64 KiB sixteen waves with the per-position arrays staged in HBM.
-Variant g_variants[kMaxTiers] = {
-    make_variant<1, 16, false, true, true>(),
-    make_variant<4, 16, false, true, true>(),
-    make_variant<16, 16, false, false, true>(),   // three arrays of 16 Ki words would not fit the 160 KB of LDS
-    make_variant<16, 64, true, true, false>(),    // whole-string horizon; arrays in HBM
+// <= 64 KiB sixteen waves with the per-position arrays staged in HBM.  Second family: the same kernels with
+// the reading of special-token marks compiled in (tables that have special tokens set).
+Variant g_variant_families[2][kMaxTiers] = {
+    {make_variant<1, 16, false, true, true, false>(), make_variant<4, 16, false, true, true, false>(),
+     make_variant<16, 16, false, false, true, false>(),   // three arrays of 16 Ki words would not fit the 160 KB of LDS
+     make_variant<16, 64, true, true, false, false>()},   // whole-string horizon; arrays in HBM
+    {make_variant<1, 16, false, true, true, true>(), make_variant<4, 16, false, true, true, true>(),
+     make_variant<16, 16, false, false, true, true>(), make_variant<16, 64, true, true, false, true>()},
 };
+Variant (&g_variants)[kMaxTiers] = g_variant_families[0];   // sizes and capacities are those of either family
 int g_tier_cap[kMaxTiers] = {0, 0, 0, 0};   // string-length bound of each tier (<= the variant's capacity)
 std::once_flag g_variants_once;
 int g_variants_status = BPE_OK;
@@ -110,7 +113,7 @@ void init_variants() {
     return;
   }
   g_num_cus = prop.multiProcessorCount;
-  for (auto& v : g_variants) {
+  for (auto& family : g_variant_families) for (auto& v : family) {
     if (v.lds > 48 * 1024) {
       if (hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds) != hipSuccess) {
         g_variants_status = BPE_EHIP;
@@ -532,7 +535,8 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   const int32_t* slot_string = nullptr;
   const int n_items_max = (int)w.max_slots;              // grid bound for the encode kernels
   // A batch that one variant's resident grid covers needs no work list: workgroup i encodes string i.
-  const bool direct = !w.split && plan.n_tiers == 1 && batch <= g_variants[0].max_grid;
+  const Variant* family = g_variant_families[cover ? 1 : 0];
+  const bool direct = !w.split && plan.n_tiers == 1 && batch <= family[0].max_grid;
   if (batch > 0) {
     if (direct) {
       list = nullptr;
@@ -599,7 +603,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     }
     size_t staged_at = w.staged;
     for (int t = 0; t < plan.n_tiers; ++t) {
-      const Variant& v = g_variants[t];
+      const Variant& v = family[t];
       int grid = v.max_grid < n_items_max ? v.max_grid : n_items_max;
       p.tier = t;
       p.staged = nullptr;

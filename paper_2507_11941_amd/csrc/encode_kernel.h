@@ -364,7 +364,7 @@ template <class M> __device__ inline M bit_at(int k) { return (M)1 << k; }
 template <class M> __device__ inline M bits_below(int k) { return ((M)1 << k) - 1; }            // k < width
 template <class M> __device__ inline M bits_above(int k) { return ~((((M)2) << k) - 1); }        // k < width
 
-template <int NW, int D, bool STAGED, bool LIMITS>
+template <int NW, int D, bool STAGED, bool LIMITS, bool SPECIAL>
 __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict__ T, uint32_t* __restrict__ V,
                               uint32_t* __restrict__ L, const BlockShared<NW>& sh) {
   static_assert(D % kGroup == 0 && D <= 64, "groups must tile the column; positions are a 64-bit mask at most");
@@ -406,7 +406,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         const int i = base + k0 + j;
         b[j] = (k0 + j <= c0 && i < n) ? src[i] : 0x100u;   // 0x100: no such byte
       }
-      if (p.cover) {                                   // uniform: special tokens are configured
+      if constexpr (SPECIAL) {                         // special tokens are configured: their marks
         const uint8_t* mark = p.cover + begin;
 #pragma unroll
         for (int j = 0; j <= kChunk; ++j) {
@@ -428,9 +428,12 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
           if (LIMITS) L[k * W + tid] = lim;
           llim = min(llim, lim);
           if (k < c0) {
-            const uint32_t w = (b[j] & kCodeSpecial) ? p.special_base + (b[j] & kCoverIndex) : sh.byte_word[b[j] & 0xFFu];
+            uint32_t w = sh.byte_word[b[j] & 0xFFu];
+            if constexpr (SPECIAL) {
+              if (b[j] & kCodeSpecial) w = p.special_base + (b[j] & kCoverIndex);
+              if (b[j] & kCodeRest) live &= ~bit_at<mask_t>(k);
+            }
             T[k * W + tid] = w;
-            if (b[j] & kCodeRest) live &= ~bit_at<mask_t>(k);
             if (k == 0) { ftok = w; firstv = v[j]; }
             if (k == c0 - 1) {
               lastv = v[j];
@@ -440,7 +443,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         }
       }
     }
-    if (p.cover) {                                     // positions may be dead from the start: look again
+    if constexpr (SPECIAL) {                           // positions may be dead from the start: look again
       ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
       firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
       lastv = live ? V[top_bit<mask_t>(live) * W + tid] : kNoRank;

@@ -60,7 +60,7 @@ struct SegRecord {
   uint32_t pad0, pad1;
 };
 
-template <int NW, int D, bool LIMITS>
+template <int NW, int D, bool LIMITS, bool SPECIAL>
 __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* __restrict__ T,
                                         uint32_t* __restrict__ V, uint32_t* __restrict__ L,
                                         const BlockShared<NW>& sh) {
@@ -103,7 +103,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       const int i = base - 1 + j;
       b[j] = (j <= c0 + 1 && c0 > 0 && i >= 0 && i < n) ? src[i] : 0x100u;
     }
-    if (p.cover) {                                     // uniform: special tokens are configured
+    if constexpr (SPECIAL) {                           // special tokens are configured: their marks
       const uint8_t* mark = p.cover + begin;
 #pragma unroll
       for (int j = 0; j < D + 2; ++j) {
@@ -129,10 +129,12 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         if (LIMITS) L[k * W + tid] = limit20_of(v);
         // (no lane-dependent branches here: positions from c0 on just get a token word nobody reads)
         const uint32_t code = b[k + 1];
-        const uint32_t plain = sh.byte_word[code & 0xFFu];
-        const uint32_t w = (code & kCodeSpecial) ? p.special_base + (code & kCoverIndex) : plain;
+        uint32_t w = sh.byte_word[code & 0xFFu];
+        if constexpr (SPECIAL) {
+          w = (code & kCodeSpecial) ? p.special_base + (code & kCoverIndex) : w;
+          live &= (code & kCodeRest) ? ~bit_at<mask_t>(k) : ~(mask_t)0;
+        }
         T[k * W + tid] = w;
-        live &= (code & kCodeRest) ? ~bit_at<mask_t>(k) : ~(mask_t)0;
         if (k == 0) { ftok = c0 > 0 ? w : ftok; firstv = c0 > 0 ? v : firstv; }
         const bool last = k == c0 - 1;
         lastv = last ? v : lastv;
@@ -140,7 +142,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         succ_tok = (last && b[k + 2] < 0x100u) ? after : succ_tok;
       }
     }
-    if (p.cover) {                                     // positions may be dead from the start
+    if constexpr (SPECIAL) {                           // positions may be dead from the start
       cuts &= live;                                    // a segment starts at a token
       ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
       firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
@@ -516,8 +518,9 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
 }
 
 // Persistent workgroups: each claims the next string of its tier until the tier's list is exhausted.
-// SEGMENTED selects encode_string_segmented() (LDS variants with at most 16 positions per lane).
-template <int NW, int D, bool STAGED, bool LIMITS, bool SEGMENTED>
+// SEGMENTED selects encode_string_segmented() (LDS variants with at most 16 positions per lane); SPECIAL
+// compiles in the reading of the special-token marks (EncodeParams::cover must then be set).
+template <int NW, int D, bool STAGED, bool LIMITS, bool SEGMENTED, bool SPECIAL>
 __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   static_assert(!(SEGMENTED && STAGED), "the segmented encoder keeps its arrays in LDS");
   constexpr int W = NW * 64;
@@ -569,8 +572,8 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   uint32_t item = blockIdx.x;
   while (item < count) {
     const int s = p.list ? (int)uniform((uint32_t)p.list[first + item]) : (int)item;
-    if constexpr (SEGMENTED) encode_string_segmented<NW, D, LIMITS>(p, s, T, V, L, sh);
-    else encode_string<NW, D, STAGED, LIMITS>(p, s, T, V, L, sh);
+    if constexpr (SEGMENTED) encode_string_segmented<NW, D, LIMITS, SPECIAL>(p, s, T, V, L, sh);
+    else encode_string<NW, D, STAGED, LIMITS, SPECIAL>(p, s, T, V, L, sh);
     if (gridDim.x >= count) break;                     // uniform: one item per workgroup at most
     // Claim the next item.  Every lane of the first wave takes part in the atomic (lane 0 adds 1, the
     // others 0) so that no lane-dependent branch sits at the loop boundary: a branch on "thread 0" here,
