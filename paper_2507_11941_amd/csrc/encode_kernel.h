@@ -172,6 +172,20 @@ struct OpParity {
   }
 };
 
+// Exclusive scan of run-parity elements over the wave from two ballots instead of a DPP chain: the element of
+// the lanes before mine is (some lane before me restarts, parity summed from the last such lane on -- or from
+// lane 0 -- up to the lane before me).  *total receives the element of the whole wave.
+__device__ inline uint32_t wave_parity_exclusive(uint32_t elem, int lane, uint32_t* total) {
+  const uint64_t par = __ballot((elem & 1u) != 0), rst = __ballot((elem & 2u) != 0);
+  const uint64_t below = (1ull << lane) - 1ull;
+  const uint64_t rb = rst & below;
+  const uint64_t from = rb ? (~0ull << (63 - __builtin_clzll(rb))) : ~0ull;
+  const uint32_t exc = (uint32_t)(__builtin_popcountll(par & below & from) & 1) | (rb ? 2u : 0u);
+  const uint64_t from_all = rst ? (~0ull << (63 - __builtin_clzll(rst))) : ~0ull;     // uniform
+  *total = (uint32_t)(__builtin_popcountll(par & from_all) & 1) | (rst ? 2u : 0u);
+  return exc;
+}
+
 // The value the lane before mine holds (lane 0 receives `identity`).
 __device__ inline uint32_t wave_shift_up(uint32_t v, uint32_t identity) {
   return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x138, 0xF, 0xF, false);  // wave_shr:1

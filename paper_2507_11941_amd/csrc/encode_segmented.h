@@ -365,10 +365,9 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     // parity of the run of left-beaten candidates that ends at the last live token before my column
     uint32_t pin;
     {
-      const uint32_t inc = wave_scan<OpParity>(elem, 0u);
-      uint32_t exc = wave_shift_up(inc, 0u);
+      uint32_t wave_total;
+      uint32_t exc = wave_parity_exclusive(elem, lane, &wave_total);
       if (NW > 1) {
-        const uint32_t wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
         if (lane == 0) sh.part[buf * NW + wave] = wave_total;
         __syncthreads();
         uint32_t before = 0;
