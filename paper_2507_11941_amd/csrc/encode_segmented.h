@@ -477,6 +477,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       TRACE_ADD(19, tq0, tp0);
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) probe_start(tab, x[j], y[j], k[j] >= 0, pf[j]);
+      for (int j = 0; j < kProbes; ++j) TRACE_LANES(20, pf[j].live ? 1 : 0);
 #ifdef BPE_TRACE
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif

@@ -61,7 +61,8 @@ def main() -> int:
     print(f"config {cfg}, batch {batch}: {int(t[10])} passes, {int(t[11])} ticks in all")
     if counts:
         print(f"  loop trips of the wave: walk1 {int(t[12])}, walk2 {int(t[13])}, probe loop {int(t[8])};  "
-              f"summed over lanes: candidates {int(t[15])}, applied {int(t[16])}, look-ups {int(t[14])}")
+              f"summed over lanes: candidates {int(t[15])}, applied {int(t[16])}, look-ups {int(t[14])}, "
+              f"of which sent to the table {int(t[20])}")
         return 0
     print(f"  inside the probe loop: operands from LDS {int(t[19])}, hash + loads + wait {int(t[17])}, "
           f"compare + store {int(t[18])}")
