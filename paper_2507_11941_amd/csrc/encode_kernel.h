@@ -348,6 +348,13 @@ __device__ unsigned long long g_trace[32];
 #define TRACE_T(var) const unsigned long long var = (blockIdx.x == 0) ? __builtin_readcyclecounter() : 0ull
 #define TRACE_ADD(slot, t0, t1) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[slot] += (t1) - (t0); } while (0)
 // one count per trip of a (possibly divergent) loop, and a sum over lanes
+#ifdef BPE_TRACE_PROBES   // clock points inside the probe loop: they lengthen it, so a build of its own
+#define TRACE_PROBE_T(var) TRACE_T(var)
+#define TRACE_PROBE_ADD(slot, t0, t1) TRACE_ADD(slot, t0, t1)
+#else
+#define TRACE_PROBE_T(var)
+#define TRACE_PROBE_ADD(slot, t0, t1)
+#endif
 #ifdef BPE_TRACE_COUNTS   // these disturb the clock figures: a build of its own
 // trips of a divergent loop that runs `cnt` times in each lane (the wave runs it max-over-lanes times), and a
 // sum over lanes
@@ -361,6 +368,8 @@ __device__ unsigned long long g_trace[32];
 #else
 #define TRACE_T(var)
 #define TRACE_ADD(slot, t0, t1)
+#define TRACE_PROBE_T(var)
+#define TRACE_PROBE_ADD(slot, t0, t1)
 #define TRACE_MAXTRIPS(slot, cnt)
 #define TRACE_LANES(slot, v)
 #endif

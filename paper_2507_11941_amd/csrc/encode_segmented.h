@@ -456,7 +456,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     TRACE_LANES(15, pop_bits<mask_t>(cm));
     TRACE_LANES(16, pop_bits<mask_t>(applied));
     while (__ballot(dirty != 0)) {
-      TRACE_T(tq0);
+      TRACE_PROBE_T(tq0);
       int k[kProbes];
       uint32_t x[kProbes], y[kProbes];
       ProbeInFlight pf[kProbes];
@@ -473,15 +473,15 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           y[j] = upper ? T[ctz_bits<mask_t>(upper) * W + tid] : succ_tok;
         }
       }
-      TRACE_T(tp0);
-      TRACE_ADD(19, tq0, tp0);
+      TRACE_PROBE_T(tp0);
+      TRACE_PROBE_ADD(19, tq0, tp0);
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) probe_start(tab, x[j], y[j], k[j] >= 0, pf[j]);
       for (int j = 0; j < kProbes; ++j) TRACE_LANES(20, pf[j].live ? 1 : 0);
-#ifdef BPE_TRACE
+#ifdef BPE_TRACE_PROBES
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif
-      TRACE_T(tp1);
+      TRACE_PROBE_T(tp1);
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) {
         if (k[j] >= 0) {
@@ -490,9 +490,9 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           if (LIMITS) L[k[j] * W + tid] = limit20_of(nv);
         }
       }
-      TRACE_T(tp2);
-      TRACE_ADD(17, tp0, tp1);
-      TRACE_ADD(18, tp1, tp2);
+      TRACE_PROBE_T(tp2);
+      TRACE_PROBE_ADD(17, tp0, tp1);
+      TRACE_PROBE_ADD(18, tp1, tp2);
     }
     if (refresh) {
       firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;

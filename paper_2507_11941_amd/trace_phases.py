@@ -1,6 +1,6 @@
 """Per-phase time breakdown of the encode kernel (developer tool).
 
-    python -m paper_2507_11941_amd.trace_phases [--counts] [config] [batch]
+    python -m paper_2507_11941_amd.trace_phases [--counts | --probes] [config] [batch]
 
 Builds a second copy of the library with -DBPE_TRACE (libbpe_hip_trace.so), encodes `batch` strings of the
 configuration once and prints, for the first string that workgroup 0 encodes, the shader-clock ticks thread 0
@@ -20,8 +20,9 @@ PHASES = ["load", "minima sweep", "scans+neighbours+candidates", "walk1", "parit
 
 
 def main() -> int:
-    args = [a for a in sys.argv[1:] if a != "--counts"]
+    args = [a for a in sys.argv[1:] if not a.startswith("--")]
     counts = "--counts" in sys.argv[1:]        # loop-trip and per-lane counts instead of clean clock figures
+    probes = "--probes" in sys.argv[1:]        # extra clock points inside the probe loop (they lengthen it)
     cfg = int(args[0]) if len(args) > 0 else 2
     batch = int(args[1]) if len(args) > 1 else 1
     import torch
@@ -29,11 +30,13 @@ def main() -> int:
     from . import _binding, build as hip_build
 
     lib_path = os.path.join(os.path.dirname(os.path.abspath(__file__)),
-                            "libbpe_hip_counts.so" if counts else "libbpe_hip_trace.so")
+                            "libbpe_hip_counts.so" if counts else
+                            "libbpe_hip_probes.so" if probes else "libbpe_hip_trace.so")
     saved = hip_build.LIB
     hip_build.LIB = lib_path
     try:
-        hip_build.build(force=False, extra_flags=("-DBPE_TRACE", "-DBPE_TRACE_COUNTS") if counts else ("-DBPE_TRACE",))   # only if missing or older than the sources
+        hip_build.build(force=False, extra_flags=("-DBPE_TRACE", "-DBPE_TRACE_COUNTS") if counts else
+                        ("-DBPE_TRACE", "-DBPE_TRACE_PROBES") if probes else ("-DBPE_TRACE",))   # only if missing or older than the sources
     finally:
         hip_build.LIB = saved
     _binding._LIB_PATH = lib_path
@@ -64,8 +67,9 @@ def main() -> int:
               f"summed over lanes: candidates {int(t[15])}, applied {int(t[16])}, look-ups {int(t[14])}, "
               f"of which sent to the table {int(t[20])}")
         return 0
-    print(f"  inside the probe loop: operands from LDS {int(t[19])}, hash + loads + wait {int(t[17])}, "
-          f"compare + store {int(t[18])}")
+    if probes:
+        print(f"  inside the probe loop: operands from LDS {int(t[19])}, hash + loads + wait {int(t[17])}, "
+              f"compare + store {int(t[18])}")
     for name, v in zip(PHASES[:10], t[:10]):
         if name == "refresh+publish":
             continue
