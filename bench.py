@@ -67,7 +67,14 @@ def cpu_baseline(merges, data, offsets, target_seconds=1.5):
     for _ in range(reps):
         table.encode_batch(data, offsets, tier=oracle.TEXTBOOK, nthreads=cores)
     wall = time.perf_counter() - t0
+    # the work model of the one-rank-per-pass view (section 4.2) on a few strings: passes and token visits
+    sample = min(len(offsets) - 1, 16)
+    _, _, st = table.encode_batch(data[: int(offsets[sample])], offsets[: sample + 1], tier=oracle.PASSES,
+                                  nthreads=cores, stats=True)
+    sample_bytes = max(int(offsets[sample]), 1)
     return {
+        "pass_view": {"strings": sample, "passes_per_string": st["passes"] / max(sample, 1),
+                      "token_visits_per_byte": st["visits"] / sample_bytes},
         "value": len(data) * reps / wall / 1e9,
         "unit": "GB/s",
         "tokens_per_s": len(ids) * reps / wall,
