@@ -502,6 +502,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     TRACE_T(t7);
     TRACE_ADD(7, t6, t7);
     TRACE_ADD(10, 0ull, 1ull);
+    TRACE_ADD(21 + (pass < 10 ? pass : 10), t0, t7);   // clock of each pass by its number
   }
   TRACE_T(t_passes);
 

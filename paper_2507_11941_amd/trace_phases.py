@@ -70,6 +70,7 @@ def main() -> int:
     if probes:
         print(f"  inside the probe loop: operands from LDS {int(t[19])}, hash + loads + wait {int(t[17])}, "
               f"compare + store {int(t[18])}")
+    print("  ticks of pass 1, 2, ...: " + ", ".join(str(int(x)) for x in t[21:32] if int(x)))
     for name, v in zip(PHASES[:10], t[:10]):
         if name == "refresh+publish":
             continue
