@@ -665,9 +665,9 @@ int bpe_read_profile(float* total_ms, int32_t* calls) {
 #ifdef BPE_TRACE
 // Debug build only: copy out (and optionally clear) the per-phase clock sums of encode_kernel.h.
 int bpe_debug_trace(unsigned long long* out, int reset) {
-  if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_trace), sizeof(unsigned long long) * 32) != hipSuccess) return BPE_EHIP;
+  if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_trace), sizeof(unsigned long long) * 128) != hipSuccess) return BPE_EHIP;
   if (reset) {
-    unsigned long long zero[32] = {0};
+    unsigned long long zero[128] = {0};
     if (hipMemcpyToSymbol(HIP_SYMBOL(bpe::g_trace), zero, sizeof(zero)) != hipSuccess) return BPE_EHIP;
   }
   return BPE_OK;

@@ -344,7 +344,7 @@ constexpr int kProbes = 2;     // table probes a lane keeps in flight (measured:
 // Optional per-phase timing (compile with -DBPE_TRACE): thread 0 of workgroup 0 accumulates the shader
 // clock spent in each phase of encode_string into g_trace; bpe_debug_trace() reads it back.
 #ifdef BPE_TRACE
-__device__ unsigned long long g_trace[32];
+__device__ unsigned long long g_trace[128];   // 0..31 sums; 32 + 8 * pass + phase for the first 12 passes
 #define TRACE_T(var) const unsigned long long var = (blockIdx.x == 0) ? __builtin_readcyclecounter() : 0ull
 #define TRACE_ADD(slot, t0, t1) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[slot] += (t1) - (t0); } while (0)
 // one count per trip of a (possibly divergent) loop, and a sum over lanes

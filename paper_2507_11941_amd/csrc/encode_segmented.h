@@ -222,6 +222,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     const uint32_t head_min = min(run, kInf20);        // over my positions before my first cut (all, if none)
     TRACE_T(t1);
     TRACE_ADD(1, t0, t1);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 1, t0, t1);
 
     // -- complete the segments that cross lanes: forward and backward segmented min-scans --
     // A lane's key is (64 - number of lanes with a cut up to it) above the minimum: a plain minimum over the
@@ -319,6 +320,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     if (NW == 1 && !__ballot(cm != 0)) break;          // a segment with pairs always has a candidate
     TRACE_T(t2);
     TRACE_ADD(2, t1, t2);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 2, t1, t2);
 
     // -- walk 1 over my candidates: which are beaten by a neighbour, and my element of the parity scan --
     // (see encode_string(); a candidate and the neighbour that beats it are always in the same segment,
@@ -362,6 +364,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     }
     TRACE_T(t3);
     TRACE_ADD(3, t2, t3);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 3, t2, t3);
     // parity of the run of left-beaten candidates that ends at the last live token before my column
     uint32_t pin;
     {
@@ -378,6 +381,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     }
     TRACE_T(t4);
     TRACE_ADD(4, t3, t4);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 4, t3, t4);
 
     // -- walk 2 over the candidates that are applied: merge --
     const mask_t applied = cm & nbr & (pin ? (e0 ^ lr) : e0);
@@ -414,6 +418,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     }
     TRACE_T(t5);
     TRACE_ADD(5, t4, t5);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 5, t4, t5);
 
     // -- who follows me now, and did the token there change? --
     {
@@ -446,6 +451,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     }
     TRACE_T(t6);
     TRACE_ADD(6, t5, t6);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 6, t5, t6);
 
     // -- look up the pairs that changed, kProbes at a time --
     const bool refresh = touched || dirty != 0;
@@ -501,6 +507,7 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     buf ^= 1;
     TRACE_T(t7);
     TRACE_ADD(7, t6, t7);
+    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 7, t6, t7);
     TRACE_ADD(10, 0ull, 1ull);
     TRACE_ADD(21 + (pass < 10 ? pass : 10), t0, t7);   // clock of each pass by its number
   }

@@ -58,7 +58,7 @@ def main() -> int:
     lib.bpe_debug_trace(None, 1)
     _binding.encode_batch(table, d, o, max_len)
     torch.cuda.synchronize()
-    t = np.zeros(32, dtype=np.uint64)
+    t = np.zeros(128, dtype=np.uint64)
     lib.bpe_debug_trace(t.ctypes.data, 0)
     passes = max(int(t[10]), 1)
     print(f"config {cfg}, batch {batch}: {int(t[10])} passes, {int(t[11])} ticks in all")
@@ -70,6 +70,12 @@ def main() -> int:
     if probes:
         print(f"  inside the probe loop: operands from LDS {int(t[19])}, hash + loads + wait {int(t[17])}, "
               f"compare + store {int(t[18])}")
+    if "--per-pass" in sys.argv[1:]:
+        print("  per pass: " + " | ".join(PHASES[1:8]))
+        for ps in range(12):
+            row = [int(t[32 + 8 * ps + ph]) for ph in range(1, 8)]
+            if any(row):
+                print(f"  pass {ps + 1:2d}: " + " ".join(f"{x:7d}" for x in row))
     print("  ticks of pass 1, 2, ...: " + ", ".join(str(int(x)) for x in t[21:32] if int(x)))
     for name, v in zip(PHASES[:10], t[:10]):
         if name == "refresh+publish":
