@@ -180,7 +180,8 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u8->i32",
+        "dtype": "u32",                           # all arithmetic is on 32-bit unsigned words (ranks, ids, masks)
+        "io": "u8 bytes in, i32 ids and i64 offsets out",
         "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg.name}", "table_merges": int(len(merges)),
                    "batch": batch, "input_bytes": total, "max_len": max_len, "tokens": n_tokens},
