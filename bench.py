@@ -35,6 +35,22 @@ def measured_traffic(config: int):
     return int(m.group(1)) if m else None
 
 
+VALU_PEAK_GIPS = 256 * 4 * 2.4 / 4      # 256 CUs x 4 SIMDs, one wave64 vector instruction per 4 cycles at 2.4 GHz
+
+
+def measured_valu(config: int):
+    """Vector wave-instructions per encode-kernel launch from the committed SQ counter summary, if it has a
+    figure for this workload."""
+    import re
+
+    try:
+        text = open(os.path.join(ROOT, "profiles", "encode_kernel_sq_counters.md")).read()
+    except OSError:
+        return None
+    m = re.search(rf"^valu_wave_instructions_per_launch_config{config}\s*=\s*(\d+)", text, flags=re.M)
+    return int(m.group(1)) if m else None
+
+
 def stream_copy_gbs(dev, nbytes=1 << 30, reps=5):
     """Read + written bytes per second of a plain device-to-device copy: the ceiling an HBM-bound kernel could
     reach on this machine, for comparison with the published peak."""
@@ -191,6 +207,11 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": kernel_ms,
                      "kernel_calls_timed": kernel_calls},
     }
+    valu = measured_valu(args.config)
+    if valu is not None:                                 # how busy the vector ALUs are: the limit that applies
+        rate = valu / (kernel_ms * 1e-3) / 1e9
+        result["issue"] = {"bound": "alu", "achieved": rate, "peak": VALU_PEAK_GIPS, "unit": "G wave-instr/s",
+                           "frac": rate / VALU_PEAK_GIPS, "valu_wave_instructions_per_launch": valu}
     if not args.no_cpu_baseline:
         result["stream_copy_GBs"] = stream_copy_gbs(dev)
         base, want = cpu_baseline(merges, data, offsets)
