@@ -1,7 +1,8 @@
 // Batch-level kernels around the per-string encoder: length binning (which kernel variant encodes which
-// string, longest strings first), the scan of token counts into out_offsets, and the packing of the
-// per-string id runs into the dense output (the paper only says that the result is an id tensor,
-// section 2.2; the dense ids + offsets layout is this library's).
+// string, longest strings first), the cutting of long strings into pieces at segment cuts, the marking of
+// special-token occurrences, the scan of token counts into out_offsets, and the packing of the per-item id
+// runs into the dense output (the paper only says that the result is an id tensor, section 2.2; the dense
+// ids + offsets layout is this library's).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

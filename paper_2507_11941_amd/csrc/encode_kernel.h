@@ -339,7 +339,8 @@ __device__ inline void publish_record(const BlockShared<NW>& sh, int buf, int wa
 
 constexpr int kChunk = 16;
 constexpr int kGroup = 4;
-constexpr int kProbes = 2;     // table probes a lane keeps in flight (measured: 1, 4 and 8 are all slower)
+constexpr int kProbes = 2;     // table probes a lane keeps in flight (measured: 1 is slower; 3, 4 and 8 cost
+                               // registers, and with them a wave of occupancy, for no shorter a string)
 
 // Optional per-phase timing (compile with -DBPE_TRACE): thread 0 of workgroup 0 accumulates the shader
 // clock spent in each phase of encode_string into g_trace; bpe_debug_trace() reads it back.
