@@ -10,9 +10,10 @@
  * Token ids: a byte b is token b (byte-level pre-tokenisation, section 4.1); the token created by row r is
  * 256 + r.  Results are exact integers; there is nothing approximate in this interface.
  *
- * Every function returns one of the BPE_* codes below (0 = success); none throws, none keeps global state
- * beyond a per-process cache of kernel attributes.  Pointers are marked HOST or DEVICE; all DEVICE pointers
- * must belong to the device that was current when the table was built.
+ * Every function returns one of the BPE_* codes below (0 = success) and none throws.  The library's only
+ * process-wide state is a cache of kernel attributes, filled on the first encode, and the optional kernel
+ * timing of bpe_set_profiling (off unless the caller switches it on).  Pointers are marked HOST or DEVICE; all
+ * DEVICE pointers must belong to the device that was current when the table was built.
  */
 #ifndef BPE_H_
 #define BPE_H_
@@ -129,18 +130,22 @@ size_t bpe_workspace_bytes(int32_t batch, int64_t total_bytes, int32_t max_len);
  * Only enqueues work on `stream`: no synchronisation, no allocation, no host reads of device data.  Once the
  * stream has drained: out_offsets[0] = 0 and out_ids[out_offsets[i] .. out_offsets[i+1]) is the encoding of
  * string i, dense and in batch order.  An empty string yields zero tokens.
- * Errors (detected before anything is enqueued): BPE_EINVAL for null pointers with non-zero sizes, negative
- * sizes, a short or misaligned workspace, or max_len out of range; BPE_EHIP if a launch fails.
+ * Errors: BPE_EINVAL for null pointers with non-zero sizes, negative sizes, a short or misaligned workspace,
+ * max_len out of range or a table of another device -- detected before anything is enqueued.  BPE_EHIP if the
+ * runtime refuses a launch or an event record: kernels launched before the failing one may already be queued,
+ * so the outputs and the workspace are then unspecified.
  */
 int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
                      int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* Timing of the per-string encode kernels alone (not the binning, offset-scan or packing kernels), for
- * roofline accounting.  bpe_set_profiling(1) switches it on and clears the record; from then on every
- * bpe_encode_batch (up to 512 calls) records a pair of HIP events on its own stream around its encode
- * kernels.  bpe_set_profiling(0) switches it off (the default).  Process-wide. */
-void bpe_set_profiling(int enabled);
+ * roofline accounting.  bpe_set_profiling(1) is a set-up call: it creates 512 pairs of HIP events (once per
+ * process), clears the record and switches the timing on; from then on every bpe_encode_batch, up to 512 calls,
+ * records one of those pairs on its own stream around its encode kernels (nothing is created or allocated in
+ * bpe_encode_batch).  bpe_set_profiling(0) switches it off, which is the default.  This state is process-wide
+ * and guarded by a mutex; switch it on only while measuring.  Returns BPE_EHIP if the events cannot be made. */
+int bpe_set_profiling(int enabled);
 
 /* Sum of the recorded encode-kernel durations in milliseconds and the number of calls recorded since
  * profiling was switched on.  total_ms, calls: HOST.  Waits for the recorded events to complete. */

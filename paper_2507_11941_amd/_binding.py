@@ -56,7 +56,7 @@ def load_library():
     lib.bpe_read_profile.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     lib.bpe_read_profile.restype = ctypes.c_int
     lib.bpe_set_profiling.argtypes = [ctypes.c_int]
-    lib.bpe_set_profiling.restype = None
+    lib.bpe_set_profiling.restype = ctypes.c_int
     lib.bpe_strerror.argtypes = [ctypes.c_int]
     lib.bpe_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -180,6 +180,11 @@ def encode_batch(table: Table, data, offsets, max_len: int, out_ids=None, out_of
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     if stream is None:
         stream = torch.cuda.current_stream(dev)
+    if stream != torch.cuda.current_stream(dev):
+        # tensors made above belong to torch's current stream: tell the allocator that `stream` uses them too,
+        # so that their memory is not handed out again while the encode kernels still run
+        for t in (out_ids, out_offsets, workspace):
+            t.record_stream(stream)
     code = lib.bpe_encode_batch(table.handle, data.data_ptr(), offsets.data_ptr(), batch, total, max_len,
                                 out_ids.data_ptr(), out_offsets.data_ptr(), workspace.data_ptr(),
                                 workspace.numel(), stream.cuda_stream)
@@ -188,7 +193,7 @@ def encode_batch(table: Table, data, offsets, max_len: int, out_ids=None, out_of
 
 
 def set_profiling(enabled: bool) -> None:
-    load_library().bpe_set_profiling(1 if enabled else 0)
+    _check(load_library().bpe_set_profiling(1 if enabled else 0), "bpe_set_profiling")
 
 
 def read_profile():

@@ -1,6 +1,7 @@
 """Build the HIP library (C ABI of include/bpe.h) for gfx950, in-tree."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
 
@@ -8,8 +9,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbpe_hip.so")
 SOURCES = [os.path.join(CSRC, "bpe.hip")]
-HEADERS = [os.path.join(CSRC, n) for n in ("table_format.h", "encode_kernel.h", "batch_kernels.h")] + [
-    os.path.join(os.path.dirname(HERE), "include", "bpe.h")]
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
+
+
+def headers():
+    """Every header the library is compiled from: a change to any of them makes the built library stale."""
+    return sorted(glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h")))
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
@@ -22,7 +27,7 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+    return any(os.path.getmtime(f) > t for f in SOURCES + headers())
 
 
 def build(force: bool = True, extra_flags=()) -> str:

@@ -4,7 +4,6 @@
 
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -80,30 +79,9 @@ Variant g_variant_families[2][kMaxTiers] = {
      make_variant<16, 16, false, false, true, true>(), make_variant<16, 64, true, true, false, true>()},
 };
 Variant (&g_variants)[kMaxTiers] = g_variant_families[0];   // sizes and capacities are those of either family
-int g_tier_cap[kMaxTiers] = {0, 0, 0, 0};   // string-length bound of each tier (<= the variant's capacity)
 std::once_flag g_variants_once;
 int g_variants_status = BPE_OK;
 int g_num_cus = 0;
-
-std::once_flag g_caps_once;
-
-void init_caps() {
-  for (int t = 0; t < kMaxTiers; ++t) g_tier_cap[t] = g_variants[t].capacity;
-  // Tuning knob: BPE_TIER_CAPS="a,b,c,d" lowers the length bounds of the four variants (0 = variant unused),
-  // e.g. "0,4096,12288,65536" sends strings up to 1 KiB to the four-wave variant as well.
-  if (const char* env = std::getenv("BPE_TIER_CAPS")) {
-    int caps[kMaxTiers];
-    if (std::sscanf(env, "%d,%d,%d,%d", &caps[0], &caps[1], &caps[2], &caps[3]) == kMaxTiers) {
-      int prev = 0;
-      bool ok = true;
-      for (int t = 0; t < kMaxTiers; ++t) {
-        ok = ok && caps[t] >= prev && caps[t] <= g_variants[t].capacity;
-        prev = caps[t];
-      }
-      if (ok) for (int t = 0; t < kMaxTiers; ++t) g_tier_cap[t] = caps[t];
-    }
-  }
-}
 
 void init_variants() {
   int dev = 0;
@@ -130,10 +108,10 @@ void init_variants() {
   }
 }
 
+// Variants that a batch with strings of up to max_len bytes can need.
 int n_tiers_for(int32_t max_len) {
-  std::call_once(g_caps_once, init_caps);
   int n = 1;
-  while (n < kMaxTiers && g_tier_cap[n - 1] < max_len) ++n;
+  while (n < kMaxTiers && g_variants[n - 1].capacity < max_len) ++n;
   return n;
 }
 
@@ -191,20 +169,12 @@ WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) 
 constexpr int kProfileRing = 512;
 struct ProfileRing {
   hipEvent_t begin[kProfileRing], end[kProfileRing];
-  int created = 0;   // event pairs that exist
+  int created = 0;   // event pairs that exist (all of them once profiling has been switched on)
   int used = 0;      // pairs recorded since profiling was switched on
 };
 ProfileRing g_prof;
 std::mutex g_prof_mutex;
 bool g_profiling = false;
-
-}  // namespace
-
-extern "C" {
-
-}  // extern "C"
-
-namespace {
 
 // The table as it lies in device memory, built in host memory: [buckets | byte_word[256] | byte_pair[65536]].
 int build_image(const int32_t* merges, int32_t n_merges, std::vector<uint32_t>& host, int& log2_buckets_out,
@@ -518,7 +488,7 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
 
   TierPlan plan;
   plan.n_tiers = n_tiers_for(max_len);
-  for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_tier_cap[t];
+  for (int t = 0; t < kMaxTiers; ++t) plan.cap[t] = g_variants[t].capacity;
 
   const uint8_t* cover = nullptr;                        // special tokens: mark their occurrences first
   if (table->d_specials && batch > 0 && total_bytes > 0) {
@@ -588,15 +558,9 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
     p.prefetch_lines = (size_t)total_bytes >= table_bytes / 4 ? (uint32_t)(table_bytes / 128) : 0u;
 
     int prof_slot = -1;
-    if (g_profiling) {
+    if (g_profiling) {                                   // the event pairs exist already: nothing is created here
       std::lock_guard<std::mutex> lock(g_prof_mutex);
-      if (g_prof.used < kProfileRing) {
-        if (g_prof.used == g_prof.created) {
-          if (hipEventCreate(&g_prof.begin[g_prof.created]) != hipSuccess ||
-              hipEventCreate(&g_prof.end[g_prof.created]) != hipSuccess)
-            return BPE_EHIP;
-          ++g_prof.created;
-        }
+      if (g_profiling && g_prof.used < g_prof.created) {
         prof_slot = g_prof.used++;
         if (hipEventRecord(g_prof.begin[prof_slot], stream) != hipSuccess) return BPE_EHIP;
       }
@@ -640,10 +604,21 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
   return hipGetLastError() == hipSuccess ? BPE_OK : BPE_EHIP;
 }
 
-void bpe_set_profiling(int enabled) {
+int bpe_set_profiling(int enabled) {
   std::lock_guard<std::mutex> lock(g_prof_mutex);
-  g_profiling = enabled != 0;
   g_prof.used = 0;
+  g_profiling = false;
+  if (!enabled) return BPE_OK;
+  while (g_prof.created < kProfileRing) {                // set-up: the only place where events are created
+    if (hipEventCreate(&g_prof.begin[g_prof.created]) != hipSuccess) return BPE_EHIP;
+    if (hipEventCreate(&g_prof.end[g_prof.created]) != hipSuccess) {
+      (void)hipEventDestroy(g_prof.begin[g_prof.created]);
+      return BPE_EHIP;
+    }
+    ++g_prof.created;
+  }
+  g_profiling = true;
+  return BPE_OK;
 }
 
 int bpe_read_profile(float* total_ms, int32_t* calls) {
@@ -661,18 +636,6 @@ int bpe_read_profile(float* total_ms, int32_t* calls) {
   *calls = g_prof.used;
   return BPE_OK;
 }
-
-#ifdef BPE_TRACE
-// Debug build only: copy out (and optionally clear) the per-phase clock sums of encode_kernel.h.
-int bpe_debug_trace(unsigned long long* out, int reset) {
-  if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(bpe::g_trace), sizeof(unsigned long long) * 128) != hipSuccess) return BPE_EHIP;
-  if (reset) {
-    unsigned long long zero[128] = {0};
-    if (hipMemcpyToSymbol(HIP_SYMBOL(bpe::g_trace), zero, sizeof(zero)) != hipSuccess) return BPE_EHIP;
-  }
-  return BPE_OK;
-}
-#endif
 
 const char* bpe_strerror(int code) {
   switch (code) {

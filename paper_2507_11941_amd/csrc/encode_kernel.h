@@ -342,39 +342,6 @@ constexpr int kGroup = 4;
 constexpr int kProbes = 2;     // table probes a lane keeps in flight (measured: 1 is slower; 3, 4 and 8 cost
                                // registers, and with them a wave of occupancy, for no shorter a string)
 
-// Optional per-phase timing (compile with -DBPE_TRACE): thread 0 of workgroup 0 accumulates the shader
-// clock spent in each phase of encode_string into g_trace; bpe_debug_trace() reads it back.
-#ifdef BPE_TRACE
-__device__ unsigned long long g_trace[128];   // 0..31 sums; 32 + 8 * pass + phase for the first 12 passes
-#define TRACE_T(var) const unsigned long long var = (blockIdx.x == 0) ? __builtin_readcyclecounter() : 0ull
-#define TRACE_ADD(slot, t0, t1) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[slot] += (t1) - (t0); } while (0)
-// one count per trip of a (possibly divergent) loop, and a sum over lanes
-#ifdef BPE_TRACE_PROBES   // clock points inside the probe loop: they lengthen it, so a build of its own
-#define TRACE_PROBE_T(var) TRACE_T(var)
-#define TRACE_PROBE_ADD(slot, t0, t1) TRACE_ADD(slot, t0, t1)
-#else
-#define TRACE_PROBE_T(var)
-#define TRACE_PROBE_ADD(slot, t0, t1)
-#endif
-#ifdef BPE_TRACE_COUNTS   // these disturb the clock figures: a build of its own
-// trips of a divergent loop that runs `cnt` times in each lane (the wave runs it max-over-lanes times), and a
-// sum over lanes
-#define TRACE_MAXTRIPS(slot, cnt) do { if (blockIdx.x == 0) { const int c_ = (cnt); int t_ = 0; \
-    while (__ballot(c_ > t_)) ++t_; if (threadIdx.x == 0) g_trace[slot] += t_; } } while (0)
-#define TRACE_LANES(slot, v) do { if (blockIdx.x == 0) atomicAdd(&g_trace[slot], (unsigned long long)(v)); } while (0)
-#else
-#define TRACE_MAXTRIPS(slot, cnt)
-#define TRACE_LANES(slot, v)
-#endif
-#else
-#define TRACE_T(var)
-#define TRACE_ADD(slot, t0, t1)
-#define TRACE_PROBE_T(var)
-#define TRACE_PROBE_ADD(slot, t0, t1)
-#define TRACE_MAXTRIPS(slot, cnt)
-#define TRACE_LANES(slot, v)
-#endif
-
 template <class M> __device__ inline int ctz_bits(M m);
 template <> __device__ inline int ctz_bits<uint32_t>(uint32_t m) { return __builtin_ctz(m); }
 template <> __device__ inline int ctz_bits<uint64_t>(uint64_t m) { return __builtin_ctzll(m); }
@@ -406,7 +373,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     if (tid == W - 1) p.counts[s] = 0;
     return;
   }
-  TRACE_T(t_start);
   const uint8_t* src = p.bytes + begin;
   const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D (uniform)
   const int dpad = (d + kGroup - 1) / kGroup * kGroup; // the sweeps read whole groups: pad with dead positions
@@ -476,14 +442,11 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
 
   int buf = 0;                                         // which half of the double-buffered exchange is current
   publish_record<NW>(sh, buf, wave, lane, live != 0, llim, firstv, lastv, ftok);
-  TRACE_T(t_loaded);
-  TRACE_ADD(0, t_start, t_loaded);
 
   // ---- merge passes ----
   // Every pass removes at least one token, so n passes can never be needed; the bound only guarantees
   // that the loop ends whatever the memory contents.
   for (int pass = 0; pass < n; ++pass) {
-    TRACE_T(t0);
     // -- the horizon E of this pass and the boundary values from the neighbouring waves --
     uint32_t E, wave_in_val = kNoRank, wave_nxt_val = kNoRank;
     if (NW == 1) {
@@ -512,8 +475,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     uint32_t nxt_val = lane_read(firstv, above ? __builtin_ctzll(above) : lane);
     if (!below) in_val = wave_in_val;
     if (!above) nxt_val = wave_nxt_val;
-    TRACE_T(t1);
-    TRACE_ADD(1, t0, t1);
 
     // -- sweep: which of my pairs are candidates --
     mask_t cm = 0;
@@ -534,8 +495,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         }
       }
     }
-    TRACE_T(t2);
-    TRACE_ADD(2, t1, t2);
 
     // -- walk 1 over my candidates: which are beaten by a neighbour, and my element of the parity scan --
     // A candidate is "beaten by its left" if the pair before it is a candidate of lower or equal rank, and
@@ -580,8 +539,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         if (is_last && prev_bl) elem = (prev_lead ? 0u : 2u) | prev_dl;
       }
     }
-    TRACE_T(t3);
-    TRACE_ADD(3, t2, t3);
     // parity of the run of left-beaten candidates that ends at the last live token before my column
     uint32_t pin;
     {
@@ -597,8 +554,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
       }
       pin = exc & 1u;
     }
-    TRACE_T(t4);
-    TRACE_ADD(4, t3, t4);
 
     // -- walk 2 over the candidates that are applied: merge --
     const mask_t applied = cm & nbr & (pin ? (e0 ^ lr) : e0);
@@ -630,8 +585,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
       dirty &= live;
       if (touched) ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
     }
-    TRACE_T(t5);
-    TRACE_ADD(5, t4, t5);
 
     // -- who follows me now, and did the token there change? --
     {
@@ -654,8 +607,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         dirty |= bit_at<mask_t>(top_bit<mask_t>(live));
       }
     }
-    TRACE_T(t6);
-    TRACE_ADD(6, t5, t6);
 
     // -- look up the pairs that changed, kProbes at a time; refresh my summary --
     const bool refresh = touched || dirty != 0;
@@ -687,8 +638,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
         }
       }
     }
-    TRACE_T(t7);
-    TRACE_ADD(7, t6, t7);
     if (__ballot(refresh)) {
       uint32_t m = kNoRank;
       for (int k0 = 0; k0 < d; k0 += kChunk) {
@@ -717,11 +666,7 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
     }
     buf ^= 1;
     publish_record<NW>(sh, buf, wave, lane, live != 0, llim, firstv, lastv, ftok);
-    TRACE_T(t8);
-    TRACE_ADD(8, t7, t8);
-    TRACE_ADD(10, 0ull, 1ull);
   }
-  TRACE_T(t_passes);
 
   // ---- emit: prefix sum of live counts gives each lane's write index (section 4.3's compaction) ----
   uint32_t total;
@@ -730,9 +675,6 @@ __device__ void encode_string(const EncodeParams& p, int s, uint32_t* __restrict
   for (mask_t m = live; m; m &= m - 1) *dst++ = (int32_t)(T[ctz_bits<mask_t>(m) * W + tid] & kTokIdMask);
   if (tid == W - 1) p.counts[s] = (int32_t)total;
   block_sync<NW>();                                    // the LDS exchange arrays are reused by the next string
-  TRACE_T(t_end);
-  TRACE_ADD(9, t_passes, t_end);
-  TRACE_ADD(11, t_start, t_end);
 }
 
 }  // namespace bpe

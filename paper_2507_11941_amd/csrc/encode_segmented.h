@@ -80,7 +80,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
     if (tid == W - 1) p.counts[s] = 0;
     return;
   }
-  TRACE_T(t_start);
   const uint8_t* src = p.bytes + begin;
   const int d = (n + W - 1) / W;                       // bytes per lane, 1 <= d <= D (uniform)
   const int dpad = (d + kGroup - 1) / kGroup * kGroup; // the sweeps work on whole groups: pad with dead positions
@@ -166,15 +165,12 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
   const uint32_t cut_after = cuts_from - (cuts ? 1u : 0u) ? kReset31 : 0u;       // some lane after me
   const int first_cut = cuts ? ctz_bits<mask_t>(cuts) : 32;
   const int last_cut = cuts ? top_bit<mask_t>(cuts) : 32;   // 32: none, every position belongs to the head
-  TRACE_T(t_loaded);
-  TRACE_ADD(0, t_start, t_loaded);
 
   // ---- merge passes ----
   // Every pass removes at least one token, so n passes can never be needed; the bound only guarantees
   // that the loop ends whatever the memory contents.
   int buf = 0;                                         // which half of the double-buffered exchange is current
   for (int pass = 0; pass < n; ++pass) {
-    TRACE_T(t0);
     // -- sweep: values and limits of my positions; minima inside my segments --
     // Per-position conditions are taken as 0 / all-ones words with bit-field extracts so that the running
     // minima are three or four vector instructions per position and no lane mask has to stay live.
@@ -220,9 +216,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       }
     }
     const uint32_t head_min = min(run, kInf20);        // over my positions before my first cut (all, if none)
-    TRACE_T(t1);
-    TRACE_ADD(1, t0, t1);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 1, t0, t1);
 
     // -- complete the segments that cross lanes: forward and backward segmented min-scans --
     // A lane's key is (64 - number of lanes with a cut up to it) above the minimum: a plain minimum over the
@@ -318,9 +311,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       }
     }
     if (NW == 1 && !__ballot(cm != 0)) break;          // a segment with pairs always has a candidate
-    TRACE_T(t2);
-    TRACE_ADD(2, t1, t2);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 2, t1, t2);
 
     // -- walk 1 over my candidates: which are beaten by a neighbour, and my element of the parity scan --
     // (see encode_string(); a candidate and the neighbour that beats it are always in the same segment,
@@ -362,9 +352,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         if (is_last && prev_bl) elem = (prev_lead ? 0u : 2u) | prev_dl;
       }
     }
-    TRACE_T(t3);
-    TRACE_ADD(3, t2, t3);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 3, t2, t3);
     // parity of the run of left-beaten candidates that ends at the last live token before my column
     uint32_t pin;
     {
@@ -379,9 +366,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       }
       pin = exc & 1u;
     }
-    TRACE_T(t4);
-    TRACE_ADD(4, t3, t4);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 4, t3, t4);
 
     // -- walk 2 over the candidates that are applied: merge --
     const mask_t applied = cm & nbr & (pin ? (e0 ^ lr) : e0);
@@ -416,9 +400,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
       dirty &= live;
       if (touched) ftok = live ? T[ctz_bits<mask_t>(live) * W + tid] : kTokNone;
     }
-    TRACE_T(t5);
-    TRACE_ADD(5, t4, t5);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 5, t4, t5);
 
     // -- who follows me now, and did the token there change? --
     {
@@ -449,20 +430,10 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
         cross |= bit_at<mask_t>(top_bit<mask_t>(live));                // my last token and the next lane's first
       dirty &= ~cross;
     }
-    TRACE_T(t6);
-    TRACE_ADD(6, t5, t6);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 6, t5, t6);
 
     // -- look up the pairs that changed, kProbes at a time --
     const bool refresh = touched || dirty != 0;
-    TRACE_MAXTRIPS(12, pop_bits<mask_t>(cm));
-    TRACE_MAXTRIPS(13, pop_bits<mask_t>(applied));
-    TRACE_MAXTRIPS(8, (pop_bits<mask_t>(dirty) + kProbes - 1) / kProbes);
-    TRACE_LANES(14, pop_bits<mask_t>(dirty));
-    TRACE_LANES(15, pop_bits<mask_t>(cm));
-    TRACE_LANES(16, pop_bits<mask_t>(applied));
     while (__ballot(dirty != 0)) {
-      TRACE_PROBE_T(tq0);
       int k[kProbes];
       uint32_t x[kProbes], y[kProbes];
       ProbeInFlight pf[kProbes];
@@ -479,15 +450,8 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           y[j] = upper ? T[ctz_bits<mask_t>(upper) * W + tid] : succ_tok;
         }
       }
-      TRACE_PROBE_T(tp0);
-      TRACE_PROBE_ADD(19, tq0, tp0);
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) probe_start(tab, x[j], y[j], k[j] >= 0, pf[j]);
-      for (int j = 0; j < kProbes; ++j) TRACE_LANES(20, pf[j].live ? 1 : 0);
-#ifdef BPE_TRACE_PROBES
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-      TRACE_PROBE_T(tp1);
 #pragma unroll
       for (int j = 0; j < kProbes; ++j) {
         if (k[j] >= 0) {
@@ -496,22 +460,13 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
           if (LIMITS) L[k[j] * W + tid] = limit20_of(nv);
         }
       }
-      TRACE_PROBE_T(tp2);
-      TRACE_PROBE_ADD(17, tp0, tp1);
-      TRACE_PROBE_ADD(18, tp1, tp2);
     }
     if (refresh) {
       firstv = live ? V[ctz_bits<mask_t>(live) * W + tid] : kNoRank;
       lastv = live ? V[top_bit<mask_t>(live) * W + tid] : kNoRank;
     }
     buf ^= 1;
-    TRACE_T(t7);
-    TRACE_ADD(7, t6, t7);
-    TRACE_ADD(32 + 8 * (pass < 12 ? pass : 11) + 7, t6, t7);
-    TRACE_ADD(10, 0ull, 1ull);
-    TRACE_ADD(21 + (pass < 10 ? pass : 10), t0, t7);   // clock of each pass by its number
   }
-  TRACE_T(t_passes);
 
   // ---- emit: prefix sum of live counts gives each lane's write index (section 4.3's compaction) ----
   uint32_t total;
@@ -520,9 +475,6 @@ __device__ void encode_string_segmented(const EncodeParams& p, int s, uint32_t* 
   for (mask_t m = live; m; m &= m - 1) *dst++ = (int32_t)(T[ctz_bits<mask_t>(m) * W + tid] & kTokIdMask);
   if (tid == W - 1) p.counts[s] = (int32_t)total;
   block_sync<NW>();                                    // the LDS exchange arrays are reused by the next string
-  TRACE_T(t_end);
-  TRACE_ADD(9, t_passes, t_end);
-  TRACE_ADD(11, t_start, t_end);
 }
 
 // Persistent workgroups: each claims the next string of its tier until the tier's list is exhausted.
