@@ -203,7 +203,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (default 5)")
+    ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (default 5); 6 = 256 strings of 64 KiB of one byte each, which "
+                         "only the HBM-staged kernel variant can take")
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle legs (baseline and comparison) and the other configurations")
     ap.add_argument("--copy-calibration", action="store_true",

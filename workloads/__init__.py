@@ -94,6 +94,9 @@ CONFIGS = {
     3: Config(3, "100k-merges 8192x4KiB", "100k", 8192, 4096, "text", 3),
     4: Config(4, "adversarial 2048x16KiB", "100k", 2048, 16384, "adversarial", 3),
     5: Config(5, "throughput 65536 lognormal", "100k", 65536, 0, "lognormal", 3),
+    # not one of the five benchmark configurations: whole 64 KiB strings of one repeated byte each, the input
+    # that has no place to cut and so exercises the encoder for strings that exceed on-chip memory
+    6: Config(6, "long runs 256x64KiB", "100k", 256, 65536, "runs", 3),
 }
 
 BATCH_SEED = 0
@@ -115,6 +118,10 @@ def batch(cfg: int, batch_override: int | None = None):
     b = c.batch if batch_override is None else int(batch_override)
     if c.kind == "text":
         data = text(c.style, BATCH_SEED, b * c.length)
+        offsets = np.arange(b + 1, dtype=np.int64) * c.length
+    elif c.kind == "runs":
+        run_bytes = np.frombuffer(b"a0 e", dtype=np.uint8)
+        data = np.repeat(run_bytes[np.arange(b) % len(run_bytes)], c.length)
         offsets = np.arange(b + 1, dtype=np.int64) * c.length
     elif c.kind == "adversarial":
         data = adversarial(BATCH_SEED, b, c.length)
