@@ -139,6 +139,23 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
                      int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* bpe_encode_batch for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and same error
+ * codes as bpe_encode_batch, without `workspace`: the kernels' scratch is a 24 MiB array that is part of the
+ * library's device code (every GPU the library runs on holds one copy until the process ends).  Limits, beyond
+ * which the call returns BPE_ETOOBIG and enqueues nothing: */
+#define BPE_STATIC_MAX_BATCH 4096
+#define BPE_STATIC_MAX_TOTAL_BYTES (4 << 20)
+#define BPE_STATIC_MAX_STRING_BYTES 16384
+/* The call allocates nothing and frees nothing (its first call on a device asks the runtime for the array's
+ * address on that device).  All calls on one GPU share that GPU's array, so two such calls must not overlap in
+ * time on one GPU -- enqueue them on one stream, or order the streams with events; calls that overlap race on
+ * the scratch and their outputs are unspecified.  Nothing in the array has to survive from call to call: the
+ * kernels reset the counters they use. */
+int bpe_encode_batch_static(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                            int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
+                            void* stream);
+
 /* Timing of the per-string encode kernels alone (not the binning, offset-scan or packing kernels), for
  * roofline accounting.  bpe_set_profiling(1) is a set-up call: it creates 512 pairs of HIP events (once per
  * process), clears the record and switches the timing on; from then on every bpe_encode_batch, up to 512 calls,

@@ -53,6 +53,8 @@ def load_library():
     lib.bpe_workspace_bytes.restype = ctypes.c_size_t
     lib.bpe_encode_batch.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.bpe_encode_batch.restype = ctypes.c_int
+    lib.bpe_encode_batch_static.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, vp]
+    lib.bpe_encode_batch_static.restype = ctypes.c_int
     lib.bpe_read_profile.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     lib.bpe_read_profile.restype = ctypes.c_int
     lib.bpe_set_profiling.argtypes = [ctypes.c_int]
@@ -189,6 +191,34 @@ def encode_batch(table: Table, data, offsets, max_len: int, out_ids=None, out_of
                                 out_ids.data_ptr(), out_offsets.data_ptr(), workspace.data_ptr(),
                                 workspace.numel(), stream.cuda_stream)
     _check(code, "bpe_encode_batch")
+    return out_ids, out_offsets
+
+
+STATIC_MAX_BATCH, STATIC_MAX_TOTAL_BYTES, STATIC_MAX_STRING_BYTES = 4096, 4 << 20, 16384
+
+
+def encode_batch_static(table: Table, data, offsets, max_len: int, out_ids, out_offsets, stream=None):
+    """bpe_encode_batch_static: the same encode with the library's built-in scratch instead of a workspace, for
+    callers that cannot allocate; outputs are the caller's.  Calls on one GPU must not overlap."""
+    import torch
+
+    lib = load_library()
+    if not (data.is_cuda and offsets.is_cuda and out_ids.is_cuda and out_offsets.is_cuda):
+        raise ValueError("encode_batch_static needs device tensors")
+    if data.dtype != torch.uint8 or offsets.dtype != torch.int64 or out_ids.dtype != torch.int32 \
+            or out_offsets.dtype != torch.int64:
+        raise ValueError("data must be uint8, offsets and out_offsets int64, out_ids int32")
+    if not (data.is_contiguous() and offsets.is_contiguous() and out_ids.is_contiguous()
+            and out_offsets.is_contiguous()):
+        raise ValueError("encode_batch_static takes contiguous tensors (it makes no copies)")
+    batch = offsets.numel() - 1
+    if out_ids.numel() < data.numel() or out_offsets.numel() < batch + 1:
+        raise ValueError("outputs too small")
+    if stream is None:
+        stream = torch.cuda.current_stream(data.device)
+    code = lib.bpe_encode_batch_static(table.handle, data.data_ptr(), offsets.data_ptr(), batch, data.numel(),
+                                       max_len, out_ids.data_ptr(), out_offsets.data_ptr(), stream.cuda_stream)
+    _check(code, "bpe_encode_batch_static")
     return out_ids, out_offsets
 
 

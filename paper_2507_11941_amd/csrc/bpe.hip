@@ -32,6 +32,15 @@ struct bpe_table {
   const SpecialSet* d_specials = nullptr;
 };
 
+// Scratch of bpe_encode_batch_static: what the caller's workspace is to bpe_encode_batch, for callers that
+// cannot allocate.  One copy per GPU the library runs on, held until the process ends; every call on a GPU
+// shares that GPU's copy.
+constexpr size_t kStaticScratchBytes = (size_t)24 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];       // device address of the array on each GPU, filled on first use
+static std::mutex g_scratch_mutex;
+
 namespace {
 
 // ---- kernel variants ------------------------------------------------------------------------------
@@ -462,19 +471,11 @@ size_t bpe_workspace_bytes(int32_t batch, int64_t total_bytes, int32_t max_len) 
   return layout_for(batch, total_bytes, max_len).total;
 }
 
-int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
-                     int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
-                     void* workspace, size_t workspace_bytes, void* stream_ptr) {
-  if (!table || batch < 0 || total_bytes < 0 || max_len < 0 || max_len > BPE_MAX_STRING_BYTES)
-    return BPE_EINVAL;
-  if (!offsets || !out_offsets || !workspace) return BPE_EINVAL;
-  if (total_bytes > 0 && (!bytes || !out_ids)) return BPE_EINVAL;
-  if (((uintptr_t)workspace & 255) != 0) return BPE_EINVAL;
-  int device = -1;
-  if (hipGetDevice(&device) != hipSuccess) return BPE_EHIP;
-  if (device != table->device) return BPE_EINVAL;
-  const WorkspaceLayout w = layout_for(batch, total_bytes, max_len);
-  if (workspace_bytes < w.total) return BPE_EINVAL;
+// Argument checks shared by the encode entry points, then the enqueue.  `workspace` is device memory of at
+// least layout_for(...).total bytes, 256-byte aligned: the caller's, or this device's static scratch array.
+static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                          int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
+                          void* workspace, const WorkspaceLayout& w, void* stream_ptr) {
 
   std::call_once(g_variants_once, init_variants);
   if (g_variants_status != BPE_OK) return g_variants_status;
@@ -602,6 +603,61 @@ int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t
                        slot_out, out_ids, table->d_id_map);
   }
   return hipGetLastError() == hipSuccess ? BPE_OK : BPE_EHIP;
+}
+
+static int check_encode_args(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                             int64_t total_bytes, int32_t max_len, const int32_t* out_ids,
+                             const int64_t* out_offsets, int* device) {
+  if (!table || batch < 0 || total_bytes < 0 || max_len < 0 || max_len > BPE_MAX_STRING_BYTES)
+    return BPE_EINVAL;
+  if (!offsets || !out_offsets) return BPE_EINVAL;
+  if (total_bytes > 0 && (!bytes || !out_ids)) return BPE_EINVAL;
+  if (hipGetDevice(device) != hipSuccess) return BPE_EHIP;
+  if (*device != table->device) return BPE_EINVAL;
+  return BPE_OK;
+}
+
+int bpe_encode_batch(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                     int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
+                     void* workspace, size_t workspace_bytes, void* stream_ptr) {
+  int device = -1;
+  const int status = check_encode_args(table, bytes, offsets, batch, total_bytes, max_len, out_ids, out_offsets,
+                                       &device);
+  if (status != BPE_OK) return status;
+  if (!workspace || ((uintptr_t)workspace & 255) != 0) return BPE_EINVAL;
+  const WorkspaceLayout w = layout_for(batch, total_bytes, max_len);
+  if (workspace_bytes < w.total) return BPE_EINVAL;
+  return encode_enqueue(table, bytes, offsets, batch, total_bytes, max_len, out_ids, out_offsets, workspace, w,
+                        stream_ptr);
+}
+
+int bpe_encode_batch_static(const bpe_table* table, const uint8_t* bytes, const int64_t* offsets, int32_t batch,
+                            int64_t total_bytes, int32_t max_len, int32_t* out_ids, int64_t* out_offsets,
+                            void* stream_ptr) {
+  int device = -1;
+  const int status = check_encode_args(table, bytes, offsets, batch, total_bytes, max_len, out_ids, out_offsets,
+                                       &device);
+  if (status != BPE_OK) return status;
+  if (batch > BPE_STATIC_MAX_BATCH || total_bytes > BPE_STATIC_MAX_TOTAL_BYTES ||
+      max_len > BPE_STATIC_MAX_STRING_BYTES)
+    return BPE_ETOOBIG;
+  const WorkspaceLayout w = layout_for(batch, total_bytes, max_len);
+  if (w.total > kStaticScratchBytes) return BPE_ETOOBIG;           // cannot happen within the three limits
+  if (device < 0 || device >= kMaxDevices) return BPE_EINVAL;
+  void* scratch = nullptr;
+  {
+    // The array's name is only a host-side handle: its device address, different on every GPU, comes from the
+    // runtime, once per device, with that device current (it is: `device` is the current one).
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) return BPE_EHIP;
+      g_scratch_ptr[device] = p;
+    }
+    scratch = g_scratch_ptr[device];
+  }
+  return encode_enqueue(table, bytes, offsets, batch, total_bytes, max_len, out_ids, out_offsets, scratch, w,
+                        stream_ptr);
 }
 
 int bpe_set_profiling(int enabled) {

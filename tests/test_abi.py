@@ -107,3 +107,17 @@ def test_encode_rejects_bad_arguments_without_a_device():
     assert lib.bpe_table_n_merges(None) == 0
     lib.bpe_free_table(None)
     assert lib.bpe_read_profile(None, None) == -1
+
+
+def test_static_entry_point_limits_fit_its_scratch():
+    """The limits of bpe_encode_batch_static are such that the workspace of any call within them fits the
+    24 MiB array the library carries (the workspace grows with each of the three sizes)."""
+    text = open(os.path.join(ROOT, "include", "bpe.h")).read()
+    lim = {k: int(eval(v)) for k, v in re.findall(r"#define (BPE_STATIC_MAX_\w+) (.+)", text)}
+    assert lim == {"BPE_STATIC_MAX_BATCH": 4096, "BPE_STATIC_MAX_TOTAL_BYTES": 4 << 20,
+                   "BPE_STATIC_MAX_STRING_BYTES": 16384}
+    worst = bpe.workspace_bytes(lim["BPE_STATIC_MAX_BATCH"], lim["BPE_STATIC_MAX_TOTAL_BYTES"],
+                                lim["BPE_STATIC_MAX_STRING_BYTES"])
+    assert 0 < worst <= 24 << 20
+    for batch, total, max_len in ((4096, 4 << 20, 1024), (1, 4 << 20, 16384), (4096, 4096, 1), (0, 0, 0)):
+        assert bpe.workspace_bytes(batch, total, max_len) <= worst
