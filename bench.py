@@ -41,9 +41,9 @@ def kernel_source_sha16() -> str:
 
 def committed_counters(config: int):
     """Figures that cannot be read from inside this process (rocprofv3 --pmc runs of this same command): HBM-side
-    bytes and vector wave-instructions per encode-kernel launch, from profiles/encode_kernel_config<C>_pmc.md.
+    bytes and vector wave-instructions per encode-kernel launch, from profiles/bpe_encode_batch_config<C>.md.
     Returns (traffic, valu, sha16 of the sources they were measured with); all None if there is no summary."""
-    path = os.path.join(ROOT, "profiles", f"encode_kernel_config{config}_pmc.md")
+    path = os.path.join(ROOT, "profiles", f"bpe_encode_batch_config{config}.md")
     try:
         text = open(path).read()
     except OSError:
@@ -271,7 +271,7 @@ def main() -> int:
                      # from the committed rocprofv3 counter runs of this command; null unless they were taken with
                      # the kernels that are running now
                      "traffic": traffic if current else None,
-                     "traffic_source": (f"profiles/encode_kernel_config{args.config}_pmc.md" if current and traffic
+                     "traffic_source": (f"profiles/bpe_encode_batch_config{args.config}.md" if current and traffic
                                         else None),
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": kernel_ms,
                      "kernel_calls_timed": kernel_calls},
@@ -280,7 +280,7 @@ def main() -> int:
         rate = valu / (kernel_ms * 1e-3) / 1e9
         result["issue"] = {"bound": "alu", "achieved": rate, "peak": VALU_PEAK_GIPS, "unit": "G wave-instr/s",
                            "frac": rate / VALU_PEAK_GIPS, "valu_wave_instructions_per_launch": valu,
-                           "source": f"profiles/encode_kernel_config{args.config}_pmc.md (same kernel sources)"}
+                           "source": f"profiles/bpe_encode_batch_config{args.config}.md (same kernel sources)"}
     if not args.no_cpu_baseline:
         import oracle
 

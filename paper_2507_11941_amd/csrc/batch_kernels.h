@@ -24,6 +24,8 @@ struct TierPlan {
 struct Control {
   uint32_t tier_base[kMaxTiers + 1];                 // start of each tier's slice of the list
   uint32_t queue_head[kMaxTiers];                    // work-queue heads of the encode kernels
+  uint32_t fallback_range[2];                        // {0, items the lane-per-segment kernel passed on}
+  uint32_t fallback_queue;                           // work-queue head of the kernel that takes those
   // used only when strings are split into pieces:
   uint32_t n_slots;                                  // piece slots in the batch
   uint32_t hist[kBinKeys];                           // pieces per (tier, length bucket)
@@ -74,6 +76,8 @@ __global__ __launch_bounds__(1024) void bin_kernel(const int64_t* offsets, int b
   }
   if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : scan[(t <= plan.n_tiers ? t : plan.n_tiers) * kLenBuckets - 1];
   if (t < kMaxTiers) c->queue_head[t] = 0;
+  if (t < 2) c->fallback_range[t] = 0;
+  if (t == 2) c->fallback_queue = 0;
   for (int s = t; s < batch; s += 1024) {
     const int64_t len = offsets[s + 1] - offsets[s];
     const int key = (len < 0 || len > 0x7FFFFFFF) ? -1 : bin_key((int)len, plan);
@@ -180,6 +184,8 @@ __global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offset
   if (blockIdx.x == 0) {
     if (tid < kBinKeys) { c->hist[tid] = 0; c->cursor[tid] = 0; }
     if (tid < kMaxTiers) c->queue_head[tid] = 0;
+    if (tid < 2) c->fallback_range[tid] = 0;
+    if (tid == 2) c->fallback_queue = 0;
   }
   // slots of all strings before the tile
   uint32_t before = 0;

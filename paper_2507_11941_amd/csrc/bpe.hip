@@ -13,6 +13,7 @@
 #include "../../include/bpe.h"
 #include "batch_kernels.h"
 #include "encode_kernel.h"
+#include "encode_lanes.h"
 #include "encode_segmented.h"
 #include "table_format.h"
 
@@ -88,6 +89,31 @@ Variant g_variant_families[2][kMaxTiers] = {
      make_variant<16, 16, false, false, true, true>(), make_variant<16, 64, true, true, false, true>()},
 };
 Variant (&g_variants)[kMaxTiers] = g_variant_families[0];   // sizes and capacities are those of either family
+
+// Items of up to 1 KiB go to the lane-per-segment kernel first; the one-wave variant above then takes those that
+// kernel passes on (items with a segment of more than 32 bytes).  [family][0]: passes them on through the
+// fallback list; [family][1]: encodes them itself (the launch without a work list).
+template <bool SPC, bool INL>
+void launch_lanes(const EncodeParams& p, int grid, hipStream_t stream) {
+  encode_lanes_kernel<SPC, INL><<<dim3(grid), dim3(64), lanes_lds_bytes<INL>(), stream>>>(p);
+}
+template <bool SPC, bool INL>
+Variant make_lanes_variant() {
+  Variant v;
+  v.waves = 1;
+  v.depth = 16;
+  v.staged = false;
+  v.limits = false;
+  v.capacity = kLaneItemBytes;
+  v.lds = lanes_lds_bytes<INL>();
+  v.fn = (const void*)&encode_lanes_kernel<SPC, INL>;
+  v.launch = &launch_lanes<SPC, INL>;
+  return v;
+}
+Variant g_lanes_variants[2][2] = {
+    {make_lanes_variant<false, false>(), make_lanes_variant<false, true>()},
+    {make_lanes_variant<true, false>(), make_lanes_variant<true, true>()},
+};
 std::once_flag g_variants_once;
 int g_variants_status = BPE_OK;
 int g_num_cus = 0;
@@ -100,7 +126,11 @@ void init_variants() {
     return;
   }
   g_num_cus = prop.multiProcessorCount;
-  for (auto& family : g_variant_families) for (auto& v : family) {
+  std::vector<Variant*> all;
+  for (auto& family : g_variant_families) for (auto& v : family) all.push_back(&v);
+  for (auto& family : g_lanes_variants) for (auto& v : family) all.push_back(&v);
+  for (Variant* vp : all) {
+    Variant& v = *vp;
     if (v.lds > 48 * 1024) {
       if (hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)v.lds) != hipSuccess) {
         g_variants_status = BPE_EHIP;
@@ -141,7 +171,7 @@ struct WorkspaceLayout {
   bool split;                        // strings are cut into pieces
   int64_t max_slots;                 // upper bound on the number of work items (strings or piece slots)
   int n_tiles;                       // scan tiles over the slots
-  size_t control, list, counts, tmp_ids, cover, staged;
+  size_t control, list, fallback, counts, tmp_ids, cover, staged;
   size_t slot_base, slot_string, piece_begin, piece_len, slot_out, tile_sum;   // split only
   size_t total;
 };
@@ -154,6 +184,7 @@ WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) 
   size_t at = 0;
   w.control = at; at += align_up(sizeof(Control));
   w.list = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
+  w.fallback = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.counts = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.tmp_ids = at; at += align_up((size_t)total_bytes * sizeof(int32_t));
   w.cover = at; at += align_up((size_t)total_bytes + 4);      // special-token marks, one per byte
@@ -507,7 +538,8 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
   const int n_items_max = (int)w.max_slots;              // grid bound for the encode kernels
   // A batch that one variant's resident grid covers needs no work list: workgroup i encodes string i.
   const Variant* family = g_variant_families[cover ? 1 : 0];
-  const bool direct = !w.split && plan.n_tiers == 1 && batch <= family[0].max_grid;
+  const Variant* lanes = g_lanes_variants[cover ? 1 : 0];
+  const bool direct = !w.split && plan.n_tiers == 1 && batch <= lanes[1].max_grid;
   if (batch > 0) {
     if (direct) {
       list = nullptr;
@@ -554,6 +586,9 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
     p.direct_count = (uint32_t)batch;
     p.cover = cover;
     p.special_base = 256u + (uint32_t)table->n_merges;
+    p.total_bytes = total_bytes;
+    p.fallback_count = &ctrl->fallback_range[1];
+    p.fallback_list = (int32_t*)(ws + w.fallback);
     // Warming L2 pays once the batch probes the table more often than it has lines: ~1 probe per input byte.
     const size_t table_bytes = table->bucket_bytes + (256 + 65536) * sizeof(uint32_t);
     p.prefetch_lines = (size_t)total_bytes >= table_bytes / 4 ? (uint32_t)(table_bytes / 128) : 0u;
@@ -576,6 +611,20 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
         if (grid > kMaxStagedGrid) grid = kMaxStagedGrid;
         p.staged = (uint32_t*)(ws + staged_at);
         staged_at += align_up(staged_slab_bytes(v) * kMaxStagedGrid);
+      }
+      if (t == 0) {
+        // one lane per segment; what it cannot take (a segment of more than 32 bytes) it encodes itself when
+        // there is no work list, and else leaves on the fallback list for the wave-per-item variant
+        const Variant& lv = lanes[direct ? 1 : 0];
+        lv.launch(p, lv.max_grid < n_items_max ? lv.max_grid : n_items_max, stream);
+        if (direct) continue;
+        EncodeParams rest = p;
+        rest.list = p.fallback_list;
+        rest.tier_base = ctrl->fallback_range;
+        rest.queue_head = &ctrl->fallback_queue;
+        rest.prefetch_lines = 0;
+        v.launch(rest, grid, stream);
+        continue;
       }
       v.launch(p, grid, stream);
     }

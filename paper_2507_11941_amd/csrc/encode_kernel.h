@@ -64,6 +64,9 @@ struct EncodeParams {
   int tier;
   const uint8_t* cover;       // null, or one mark per input byte: where the special tokens lie (see kCover*)
   uint32_t special_base;      // token number of special 0 (256 + rows)
+  int64_t total_bytes;        // size of `bytes`: wide loads must not run past it
+  uint32_t* fallback_count;   // lane-per-segment kernel: items it cannot take are counted here ...
+  int32_t* fallback_list;     // ... and listed here, for the wave-per-item kernel that runs after it
 };
 
 // What the load phases make of them: "byte codes" above the byte values.  Any code >= 0x100 is no byte, so
