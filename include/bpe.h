@@ -60,7 +60,7 @@ int bpe_build_table(const int32_t* merges, int32_t n_merges, bpe_table** out, in
 
 /* The table bpe_build_table would upload, built in HOST memory instead (no device is touched): for callers
  * that want to inspect or cache it, and for tests of the builder.  Layout, in uint32 words:
- *   [buckets: 2^log2_buckets x 4 slots x {value, tag}] [token word of each byte: 256] [byte-pair table: 65536]
+ *   [buckets: 2^log2_buckets x 2 slots x {value, tag}] [token word of each byte: 256] [byte-pair table: 65536]
  * (section 4.3's hashmap; the format is described in paper_2507_11941_amd/csrc/table_format.h).
  *   merges, n_merges, bad_row  as for bpe_build_table (same validation, same codes).
  *   words         HOST, uint32[capacity]; may be NULL when capacity is 0 (size query).

@@ -266,7 +266,6 @@ int build_image(const int32_t* merges, int32_t n_merges, std::vector<uint32_t>& 
   for (;; ++log2_buckets) {                                    // grow until every key sits close to home
     if (log2_buckets > kMaxLog2Buckets) return BPE_ETOOBIG;
     const size_t n_buckets = (size_t)1 << log2_buckets;
-    const uint32_t bucket_mask = (uint32_t)n_buckets - 1;
     n_words = n_buckets * kSlotsPerBucket * 2;                 // uint32 words
     try {
       host.assign(n_words + 256 + 65536, 0xFFFFFFFFu);
@@ -288,9 +287,10 @@ int build_image(const int32_t* merges, int32_t n_merges, std::vector<uint32_t>& 
       if (a < 256 && b < 256) host[n_words + 256 + (a << 8 | b)] = value;   // direct table for byte pairs
       const Placement pl = place_pair(a, b, log2_buckets);
       bool placed = false;
-      for (uint32_t step = 0; step <= kMaxDisplacement && !placed; ++step) {
-        uint32_t* bucket = host.data() + (size_t)((pl.bucket + step) & bucket_mask) * kSlotsPerBucket * 2;
-        const uint32_t tag = slot_tag(pl.fingerprint, step);
+      uint32_t* const home = host.data() + (size_t)pl.bucket * kSlotsPerBucket * 2;
+      for (uint32_t d = 0; d <= kMaxDisplacement && !placed; ++d) {       // home bucket, then the rest of its line
+        uint32_t* bucket = host.data() + (size_t)(pl.bucket ^ d) * kSlotsPerBucket * 2;
+        const uint32_t tag = slot_tag(pl.fingerprint, d);
         for (int k = 0; k < kSlotsPerBucket; ++k) {
           uint32_t& slo = bucket[2 * k];
           uint32_t& shi = bucket[2 * k + 1];
@@ -304,6 +304,11 @@ int build_image(const int32_t* merges, int32_t n_merges, std::vector<uint32_t>& 
             if (bad_row) *bad_row = r;
             return BPE_EDUPPAIR;
           }
+        }
+        // the home bucket is full (else the key would be in it): its spare bits say how far its keys reach
+        if (placed && d > bucket_reach(home[0], home[2])) {
+          home[0] = (home[0] & ~3u) | (d & 3u);
+          home[2] = (home[2] & ~3u) | (d >> 2);
         }
       }
       fits = placed;
@@ -573,7 +578,6 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
     p.table.byte_word = (const uint32_t*)((const char*)table->d_mem + table->bucket_bytes);
     p.table.byte_pair = p.table.byte_word + 256;
     p.table.log2_buckets = table->log2_buckets;
-    p.table.bucket_mask = ((uint32_t)1 << table->log2_buckets) - 1;
     p.bytes = bytes;
     p.offsets = offsets;
     p.piece_begin = piece_begin;

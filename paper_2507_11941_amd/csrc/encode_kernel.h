@@ -40,11 +40,10 @@
 namespace bpe {
 
 struct DeviceTable {
-  const uint4* buckets;       // 2 x uint4 per bucket
+  const uint4* buckets;       // one uint4 per bucket
   const uint32_t* byte_word;  // [256] token word (id | capability bits) of each byte
   const uint32_t* byte_pair;  // [256*256] value of the pair (byte a, byte b) at a*256 + b, kNoRank if none
   int log2_buckets;
-  uint32_t bucket_mask;
 };
 
 struct EncodeParams {
@@ -197,31 +196,10 @@ __device__ inline uint32_t wave_shift_up(uint32_t v, uint32_t identity) {
 // ---------------------------------------------------------------------------------------------------
 // table probe
 
-__device__ inline uint32_t probe_ids(const DeviceTable& t, uint32_t a, uint32_t b) {
-  const Placement pl = place_pair(a, b, t.log2_buckets);
-  for (uint32_t step = 0; step <= kMaxDisplacement; ++step) {
-    const uint4* p = t.buckets + 2 * (size_t)((pl.bucket + step) & t.bucket_mask);
-    const uint4 x = p[0], y = p[1];
-    const uint32_t tag = slot_tag(pl.fingerprint, step);
-    if (x.y == tag) return x.x;
-    if (x.w == tag) return x.z;
-    if (y.y == tag) return y.x;
-    if (y.w == tag) return y.z;
-    if (y.w == 0xFFFFFFFFu) break;            // bucket not full: the key is nowhere else
-  }
-  return kNoRank;
-}
-
-// Value of the pair of two token words, skipping the probe when the capability bits rule it out.
-__device__ inline uint32_t probe_words(const DeviceTable& t, uint32_t x, uint32_t y) {
-  if (!(x & kTokCanLeft) || !(y & kTokCanRight)) return kNoRank;
-  return probe_ids(t, x & kTokIdMask, y & kTokIdMask);
-}
-
-// The same lookup split in two so that a lane can have several probes in flight: start() issues the two
-// 16-byte loads of the home bucket, finish() inspects them (and walks on in the rare displaced case).
+// The lookup is split in two so that a lane can have several in flight: start() issues the one 16-byte load of
+// the home bucket, finish() inspects it (and reads on along the line in the overflow case).
 struct ProbeInFlight {
-  uint4 x, y;
+  uint4 q;          // the home bucket: two slots of {value, tag}
   Placement pl;
   bool live;        // false: the capability bits or a missing neighbour already decided "no pair"
 };
@@ -230,32 +208,26 @@ __device__ inline void probe_start(const DeviceTable& t, uint32_t xw, uint32_t y
   f.live = wanted && yw != kTokNone && (xw & kTokCanLeft) && (yw & kTokCanRight);
   if (f.live) {
     f.pl = place_pair(xw & kTokIdMask, yw & kTokIdMask, t.log2_buckets);
-    const uint4* p = t.buckets + 2 * (size_t)f.pl.bucket;
-    f.x = p[0];
-    f.y = p[1];
+    f.q = t.buckets[f.pl.bucket];
   }
 }
 
+// Value of the slot whose tag matches, kNoRank if neither does (selects, not branches).
+__device__ inline uint32_t match_bucket(const uint4& q, uint32_t tag) {
+  uint32_t found = q.y == tag ? q.x : kNoRank;
+  return q.w == tag ? q.z : found;
+}
+
 __device__ inline uint32_t probe_finish(const DeviceTable& t, const ProbeInFlight& f) {
-  const uint32_t tag = slot_tag(f.pl.fingerprint, 0);
-  uint32_t found = kNoRank;                            // at most one slot matches: selects, not branches
-  found = f.x.y == tag ? f.x.x : found;
-  found = f.x.w == tag ? f.x.z : found;
-  found = f.y.y == tag ? f.y.x : found;
-  found = f.y.w == tag ? f.y.z : found;
+  uint32_t found = match_bucket(f.q, slot_tag(f.pl.fingerprint, 0));
   if (!f.live) return kNoRank;
-  if (found != kNoRank || f.y.w == 0xFFFFFFFFu) return found;
-  for (uint32_t step = 1; step <= kMaxDisplacement; ++step) {   // home bucket full: the key may be displaced
-    const uint4* p = t.buckets + 2 * (size_t)((f.pl.bucket + step) & t.bucket_mask);
-    const uint4 x = p[0], y = p[1];
-    const uint32_t tg = slot_tag(f.pl.fingerprint, step);
-    if (x.y == tg) return x.x;
-    if (x.w == tg) return x.z;
-    if (y.y == tg) return y.x;
-    if (y.w == tg) return y.z;
-    if (y.w == 0xFFFFFFFFu) break;
+  if (found == kNoRank && f.q.w != 0xFFFFFFFFu) {
+    // my home bucket is full: keys of it may have been displaced, and mine, if it exists, is then one of them
+    const uint32_t reach = bucket_reach(f.q.x, f.q.z);
+    for (uint32_t d = 1; d <= reach && found == kNoRank; ++d)
+      found = match_bucket(t.buckets[f.pl.bucket ^ d], slot_tag(f.pl.fingerprint, d));
   }
-  return kNoRank;
+  return found == kNoRank ? kNoRank : (found & ~kValueSpare);
 }
 
 // ---------------------------------------------------------------------------------------------------

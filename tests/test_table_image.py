@@ -17,24 +17,37 @@ NO_RANK, CUT = 0xFFFFFFFF, 0xFFFFFFFD
 M32 = 0xFFFFFFFF
 
 
+SLOTS = 2                                        # per bucket; a bucket is 16 bytes, eight share a 128-byte line
+FLAG_LEFT, FLAG_RIGHT, HORIZON_SHIFT = 1 << 10, 1 << 11, 2
+
+
+def mul24(x, y):
+    return ((x & 0xFFFFFF) * (y & 0xFFFFFF)) & M32
+
+
 def place_pair(a, b, log2_buckets):
-    b2 = b ^ (((a * 0x9E3779B1) & M32) >> 12)
-    a2 = a ^ (((b2 * 0x85EBCA77) & M32) >> 12)
+    b2 = b ^ (mul24(a, 0x9E3779) >> 12)
+    a2 = a ^ (mul24(b2, 0x85EBCB) >> 12)
     return a2 & ((1 << log2_buckets) - 1), ((a2 >> log2_buckets) << 20) | b2
 
 
 def lookup(words, log2_buckets, a, b):
-    """Value stored for (a, b) or NO_RANK, walking the buckets as the format prescribes."""
+    """Value stored for (a, b) or NO_RANK, reading the buckets as the format prescribes: the home bucket, and
+    the buckets bucket ^ 1 .. bucket ^ d of its line only where the home bucket is full and records, in spare
+    value bits of its two slots, that its keys reach as far as displacement d."""
     bucket, fp = place_pair(a, b, log2_buckets)
-    mask = (1 << log2_buckets) - 1
-    for step in range(3):
-        base = ((bucket + step) & mask) * 8
-        slots = words[base:base + 8]
-        for k in range(4):
-            if int(slots[2 * k + 1]) == (fp | (step << 30)):
-                return int(slots[2 * k])
-        if int(slots[7]) == M32:                 # last slot empty: the key cannot be further on
-            break
+    assert fp < 1 << 27
+    home = [int(x) for x in words[bucket * 2 * SLOTS:(bucket + 1) * 2 * SLOTS]]
+    for k in range(SLOTS):
+        if home[2 * k + 1] == fp:
+            return home[2 * k] & ~3
+    if home[3] != M32:
+        reach = (home[0] & 3) | ((home[2] & 3) << 2)
+        for d in range(1, reach + 1):
+            other = [int(x) for x in words[(bucket ^ d) * 2 * SLOTS:((bucket ^ d) + 1) * 2 * SLOTS]]
+            for k in range(SLOTS):
+                if other[2 * k + 1] == (fp | (d << 28)):
+                    return other[2 * k] & ~3
     return NO_RANK
 
 
@@ -58,9 +71,9 @@ def check_image(merges):
     merges = [tuple(map(int, r)) for r in merges]
     n = len(merges)
     words, log2 = bpe.table_image(merges)
-    n_bucket_words = (1 << log2) * 8
+    n_bucket_words = (1 << log2) * 2 * SLOTS
     assert len(words) == n_bucket_words + 256 + 65536
-    assert 4 * (1 << log2) * 2 >= 5 * n                       # load at most 0.4
+    assert SLOTS * (1 << log2) * 2 >= 5 * n                   # load at most 0.4
     byte_word = words[n_bucket_words:n_bucket_words + 256]
     byte_pair = words[n_bucket_words + 256:]
 
@@ -74,9 +87,9 @@ def check_image(merges):
         v = lookup(words, log2, a, b)
         assert v != NO_RANK and v >> 12 == r, (r, a, b)
         tok = 256 + r
-        assert bool(v & 2) == (tok in first_left) and bool(v & 4) == (tok in first_right)
+        assert bool(v & FLAG_LEFT) == (tok in first_left) and bool(v & FLAG_RIGHT) == (tok in first_right)
         uses = [x for x in (first_left.get(tok), first_right.get(tok)) if x is not None]
-        code = (v >> 4) & 0xFF
+        code = (v >> HORIZON_SHIFT) & 0xFF
         if uses:
             limit = r + 1 + horizon_decode(code)
             assert code != 255 and r < limit <= min(uses), (r, limit, uses)
@@ -85,7 +98,7 @@ def check_image(merges):
         else:
             assert code == 255
         if a < 256 and b < 256:
-            assert int(byte_pair[a << 8 | b]) == v
+            assert int(byte_pair[a << 8 | b]) == v     # (the direct table never carries the overflow bit)
     # the occupied slots are exactly the rows
     tags = words[1:n_bucket_words:2]
     assert int((tags != M32).sum()) == n
@@ -142,10 +155,10 @@ def test_doubling_chain_horizons():
     for r, (a, b) in enumerate(rows):
         v = lookup(words, log2, a, b)
         assert v >> 12 == r
-        assert ((v >> 4) & 0xFF) == (0 if r + 1 < len(rows) else 255)
+        assert ((v >> HORIZON_SHIFT) & 0xFF) == (0 if r + 1 < len(rows) else 255)
 
 
-@pytest.mark.parametrize("key", ["1k", "32k"])
+@pytest.mark.parametrize("key", ["1k", "32k", "100k"])
 def test_trained_tables(key):
     check_image(workloads.load_merges(key))
 
