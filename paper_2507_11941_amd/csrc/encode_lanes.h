@@ -12,8 +12,10 @@
 //   load     position-parallel, one row of 64 consecutive bytes at a time: lane t holds byte 64 j + t of row j
 //            (coalesced byte loads, conflict-free LDS traffic), looks its pair with the next byte up in the direct
 //            byte-pair table, and a ballot of "this pair is a cut" is the row's piece of the segment-end bitmap.
-//   list     first positions of the segments with at least two bytes, from the same ballots; segments of more
-//            than 8 bytes are listed from the front, the others from the back.
+//   list     the segments with at least two bytes (first position and length), from the same ballots, then sorted
+//            by length, longest first: a counting sort with one LDS counter per length.  Handing the long
+//            segments out first is what keeps the lanes level at the end of an item (a third fewer trips of the
+//            merge loop than in text order).
 //   merge    segment-parallel, as above; a lane keeps its segment's liveness as a 32-bit mask, so a segment
 //            may have at most 32 bytes.  An item with a longer segment is not encoded here: the kernel hands
 //            it to the wave-per-item encoder of encode_segmented.h, which has no such limit.
@@ -48,8 +50,9 @@ struct LaneLds {
   static constexpr int kT = 0;                                          // token word of every position
   static constexpr int kV = kT + kLaneItemBytes + kLanePad;             // pair value of every position
   static constexpr int kEnds = kV + kLaneItemBytes + kLanePad;          // bit p: position p ends its segment
-  static constexpr int kSeg = kEnds + kLaneItemBytes / 32 + 4;          // uint16: first position of each segment
-  static constexpr int kWords = kSeg + kLaneItemBytes / 4;
+  static constexpr int kSeg = kEnds + kLaneItemBytes / 32 + 4;          // uint16: first position | (length - 1) << 10
+  static constexpr int kHist = kSeg + kLaneItemBytes / 4;               // segments of each length, then list bases
+  static constexpr int kWords = kHist + 32;
 };
 
 __device__ inline uint32_t mbcnt64(uint64_t mask) {                     // set bits of mask below my lane
@@ -66,7 +69,7 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
   uint32_t* const V = lds + LaneLds::kV;
   uint32_t* const ends = lds + LaneLds::kEnds;
   uint16_t* const seg = (uint16_t*)(lds + LaneLds::kSeg);
-  constexpr uint32_t kSegSlots = kLaneItemBytes / 2;
+  uint32_t* const hist = lds + LaneLds::kHist;
 
   const int64_t begin = p.piece_begin ? p.piece_begin[s] : p.offsets[s];
   const int n = (int)uniform((uint32_t)(p.piece_len ? p.piece_len[s] : (int32_t)(p.offsets[s + 1] - begin)));
@@ -77,7 +80,7 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
   const int rows = (n + 63) >> 6;                      // uniform
 
   // ---- load: byte-level pre-tokenisation (section 4.1), the initial pair values, segment ends and starts ----
-  uint32_t n_long = 0, n_short = 0;                    // segments listed from the front / from the back (uniform)
+  uint32_t n_segments = 0;                             // segments with a pair to look at (uniform)
   {
     const uint8_t* src = p.bytes + begin + lane;
     uint32_t b[kLaneRows + 1], mk[kLaneRows + 1];
@@ -128,28 +131,63 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
         // segments that start in this row and hold a pair: after an end, and not an end themselves
         const uint64_t start_row = ((end_row << 1) | carry) & ~end_row;
         carry = end_row >> 63;
-        // "long": no end among the next 8 positions (judged inside the row: the order of the list only
-        // balances the lanes' work)
-        const uint64_t e2 = end_row | (end_row >> 1), e4 = e2 | (e2 >> 2), near_end = e4 | (e4 >> 4);
-        const uint64_t long_row = start_row & ~near_end, short_row = start_row & near_end;
-        if ((long_row >> lane) & 1ull) seg[n_long + mbcnt64(long_row)] = (uint16_t)pos;
-        if ((short_row >> lane) & 1ull) seg[kSegSlots - 1u - n_short - mbcnt64(short_row)] = (uint16_t)pos;
-        n_long += (uint32_t)__builtin_popcountll(long_row);
-        n_short += (uint32_t)__builtin_popcountll(short_row);
+        if ((start_row >> lane) & 1ull) seg[n_segments + mbcnt64(start_row)] = (uint16_t)pos;
+        n_segments += (uint32_t)__builtin_popcountll(start_row);
       }
     }
     if (lane < 4) ends[2 * rows + lane] = 0xFFFFFFFFu;                   // a window never runs past the item
+    if (lane < 32) hist[lane] = 0;
   }
-  const uint32_t n_segments = n_long + n_short;
   __syncthreads();                                     // one wave: orders the LDS traffic of the phases
+
+  // ---- list, sorted: longest segments first (counting sort over the 31 possible lengths) ----
+  {
+    constexpr int kRounds = kLaneItemBytes / 2 / 64;   // at most 512 segments of two bytes
+    uint32_t entry[kRounds], place[kRounds];
+    bool too_long = false;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      entry[r] = 0;
+      place[r] = 0;
+      if ((uint32_t)(64 * r) < n_segments) {           // uniform
+        const uint32_t i = 64u * r + (uint32_t)lane;
+        if (i < n_segments) {
+          const uint32_t first = seg[i];
+          // the segment ends at the first set bit of the ends bitmap from `first` on
+          const uint32_t window = __builtin_amdgcn_alignbit(ends[(first >> 5) + 1], ends[first >> 5], first & 31u);
+          too_long |= window == 0;
+          const uint32_t len = window ? (uint32_t)__builtin_ctz(window) + 1u : 2u;      // 2..32
+          entry[r] = first | ((len - 1u) << 10);
+          place[r] = atomicAdd(&hist[32u - len], 1u);  // my place among the segments of my length
+        }
+      }
+    }
+    if (__ballot(too_long)) return false;              // a segment no lane can take (nothing has left LDS)
+    __syncthreads();
+    {
+      const uint32_t mine = lane < 32 ? hist[lane] : 0u;
+      const uint32_t inc = wave_scan<OpAdd>(mine, 0u);
+      __syncthreads();
+      if (lane < 32) hist[lane] = inc - mine;          // where the segments of length 32 - lane start
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      if ((uint32_t)(64 * r) < n_segments) {           // uniform
+        if (64u * r + (uint32_t)lane < n_segments)
+          seg[hist[31u - (entry[r] >> 10)] + place[r]] = (uint16_t)entry[r];
+      }
+    }
+  }
+  __syncthreads();
 
   // ---- merge: Algorithm 1 on one segment per lane ----
   // The look-ups of the two pairs a merge creates stay in flight over the loop's edge: the next trip first scans
   // the pair values that did not change and only then takes the two new ones.
   uint32_t dead = 0xFFFFFFFFu;     // bit o: position o of my segment holds no token; all ones: I have no segment
-  uint32_t s4 = 0;                 // byte offset of my segment's first position in T and V
+  uint32_t* t0 = T;                // my segment's first position in T ...
+  uint32_t* v0 = V;                // ... and in V
   uint32_t next = 0;               // first segment nobody has taken (uniform)
-  bool too_long = false;
   ProbeInFlight f1, f2;            // (left token, merged token) and (merged token, token after it)
   f1.q = f2.q = make_uint4(0, 0, 0, 0);
   f1.pl.bucket = f1.pl.fingerprint = f2.pl.bucket = f2.pl.fingerprint = 0;
@@ -159,30 +197,27 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
   uint32_t pk = 0, pl = 0;         // ... the merged token's position and its left neighbour's
   // Every trip ends a segment or removes a token in each lane that has a segment, so 2 n trips cannot be needed;
   // the bound only guarantees that the loop ends whatever the memory contents.
-  for (int trip = 0; trip < 2 * n + 64; ++trip) {
-    {
-      const bool idle = dead == 0xFFFFFFFFu;           // (an idle lane has nothing in flight)
-      const uint64_t idle_lanes = __ballot(idle);
-      if (idle_lanes && next < n_segments) {           // uniform
-        const uint32_t mine = next + mbcnt64(idle_lanes);
-        next += (uint32_t)__builtin_popcountll(idle_lanes);
-        if (idle && mine < n_segments) {
-          const uint32_t first = seg[mine < n_long ? mine : kSegSlots - 1u - (mine - n_long)];
-          // the segment ends at the first set bit of the ends bitmap from `first` on
-          const uint32_t window = __builtin_amdgcn_alignbit(ends[(first >> 5) + 1], ends[first >> 5], first & 31u);
-          too_long |= window == 0;
-          const uint32_t len = window ? (uint32_t)__builtin_ctz(window) + 1u : 1u;
-          dead = len >= 32u ? 0u : 0xFFFFFFFFu << len;
-          s4 = first * 4u;
-        }
+  // A lane without a segment takes the next one of the list.
+  auto take_segments = [&]() {
+    const bool idle = dead == 0xFFFFFFFFu;             // (an idle lane has nothing in flight)
+    const uint64_t idle_lanes = __ballot(idle);
+    if (idle_lanes && next < n_segments) {             // uniform
+      const uint32_t mine = next + mbcnt64(idle_lanes);
+      next += (uint32_t)__builtin_popcountll(idle_lanes);
+      if (idle && mine < n_segments) {
+        const uint32_t e = seg[mine];
+        const uint32_t first = e & 1023u, len = (e >> 10) + 1u;
+        dead = len >= 32u ? 0u : 0xFFFFFFFFu << len;
+        t0 = T + first;
+        v0 = V + first;
       }
     }
-    if (__ballot(too_long)) return false;              // (nothing has left LDS yet)
+  };
+  take_segments();
+  for (int trip = 0; trip < 2 * n + 64; ++trip) {
     if (!__ballot(dead != 0xFFFFFFFFu)) break;         // every segment is done
 
     // the lowest value among my live pairs, left-most on ties: the position rides in the low bits
-    uint32_t* const t0 = (uint32_t*)((char*)T + s4);
-    uint32_t* const v0 = (uint32_t*)((char*)V + s4);
     uint32_t best = 0xFFFFFFFFu;
     {
       const uint32_t skip = dead | hold;
@@ -242,6 +277,7 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
       probe_start(tab, x1, y1, pending_left, f1);
       probe_start(tab, x2, y2, merge, f2);
     }
+    take_segments();                                   // lanes whose segment just ended go on at once
   }
   __syncthreads();
 
