@@ -308,6 +308,11 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   extern __shared__ uint32_t smem[];
   uint32_t* const byte_word = smem;                    // [256], then the per-item arrays
   uint32_t* const arrays = smem + 256;
+  const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
+  const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
+  // items per claim: as many as keep every workgroup of the grid busy, kLaneChunk at most
+  const uint32_t per_claim = min(kLaneChunk, max(1u, count / gridDim.x));
+  if (blockIdx.x * per_claim >= count) return;         // uniform: nothing for this workgroup
   for (int i = (int)threadIdx.x; i < 256; i += 64) byte_word[i] = p.table.byte_word[i];
 
   // warm this XCD's L2 with the merge table (see encode_kernel)
@@ -324,12 +329,9 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   }
   __syncthreads();
 
-  const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
-  const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
   // Items are claimed kLaneChunk at a time: the first chunk of a workgroup is its own index, later ones come from
   // the tier's queue head (which starts at zero).  One claim per item would make every wave wait for a round trip
   // to the one contended address after each item.
-  const uint32_t per_claim = gridDim.x >= count ? 1u : kLaneChunk;     // a grid that covers the list: one item each
   uint32_t chunk = blockIdx.x;
   while (chunk * per_claim < count) {
     for (uint32_t item = chunk * per_claim; item < min((chunk + 1) * per_claim, count); ++item) {

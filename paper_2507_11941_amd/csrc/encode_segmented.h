@@ -497,6 +497,12 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
     L = cur;
     if (LIMITS) cur += W * D;
   }
+  // Work items: the first one is my workgroup index, later ones come from the tier's atomic counter (which
+  // starts at zero and is offset by the grid size).  When the grid covers the whole list no atomic is needed.
+  // (With a single variant in use and a grid that covers the batch there is no list at all: item = string.)
+  const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
+  const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
+  if (blockIdx.x >= count) return;                     // uniform: nothing for this workgroup (often: an empty tier)
   BlockShared<NW> sh;
   sh.rec = (WaveRecord*)cur; cur += 2 * NW * 8;        // room for either record type
   sh.first_tok = cur; cur += 2 * NW;
@@ -524,11 +530,6 @@ __global__ __launch_bounds__(NW * 64) void encode_kernel(EncodeParams p) {
   }
   __syncthreads();
 
-  // Work items: the first one is my workgroup index, later ones come from the tier's atomic counter (which
-  // starts at zero and is offset by the grid size).  When the grid covers the whole list no atomic is needed.
-  // (With a single variant in use and a grid that covers the batch there is no list at all: item = string.)
-  const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
-  const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
   uint32_t item = blockIdx.x;
   while (item < count) {
     const int s = p.list ? (int)uniform((uint32_t)p.list[first + item]) : (int)item;
