@@ -47,6 +47,8 @@ def _load():
         lib.orc_encode.restype = i64
         lib.orc_encode_batch.argtypes = [vp, ci, vp, vp, i64, ci, vp, vp, vp]
         lib.orc_encode_batch.restype = i64
+        lib.orc_pass_trace.argtypes = [vp, vp, i64, vp, i64]
+        lib.orc_pass_trace.restype = i64
         lib.orc_decode.argtypes = [vp, vp, i64, vp, i64]
         lib.orc_decode.restype = i64
         lib.orc_train.argtypes = [vp, i64, i32, vp, ci]
@@ -111,6 +113,15 @@ class Table:
         if stats:
             return ids, {"passes": int(st[0]), "visits": int(st[1]), "merges": int(st[2])}
         return ids
+
+    def pass_trace(self, s):
+        """What each pass of the pass view (one rank per pass, section 4.2) did on s: a list of
+        (rank applied, live tokens at the start of the pass, merges applied by the pass)."""
+        b = _as_bytes(s)
+        cap = max(len(b), 1)
+        out = np.zeros(3 * cap, dtype=np.int64)
+        passes = _load().orc_pass_trace(self._h, b.ctypes.data, len(b), out.ctypes.data, cap)
+        return [tuple(int(x) for x in out[3 * i:3 * i + 3]) for i in range(min(passes, cap))]
 
     def encode_batch(self, data, offsets, tier: int = TEXTBOOK, nthreads: int = 1, stats: bool = False):
         """Dense (ids int32[total_tokens], out_offsets int64[B+1]) for a batch of strings."""

@@ -135,6 +135,9 @@ struct PassStats {
   int64_t passes = 0;        // number of merge passes (distinct ranks applied)
   int64_t visits = 0;        // sum over passes of the live token count at the start of the pass
   int64_t merges = 0;        // total merges applied
+  // what each pass did, for the checks of the pass invariants (kept only when asked for):
+  bool keep_trace = false;
+  std::vector<int64_t> trace;   // per pass: rank applied, live tokens at its start, merges it applied
 };
 
 // Pass view of section 4.2: one rank per pass, every non-overlapping occurrence, left-most first.
@@ -146,6 +149,8 @@ std::vector<int32_t> encode_passes(const Table& t, const uint8_t* s, int64_t n, 
     if (best == kNoRank) break;
     const int32_t a = t.rows[(size_t)best].first, b = t.rows[(size_t)best].second;
     if (st) { st->passes += 1; st->visits += (int64_t)T.size(); }
+    const size_t live_before = T.size();
+    int64_t merges_before = st ? st->merges : 0;
     std::vector<int32_t> next;
     next.reserve(T.size());
     size_t i = 0;
@@ -158,6 +163,11 @@ std::vector<int32_t> encode_passes(const Table& t, const uint8_t* s, int64_t n, 
         next.push_back(T[i]);
         i += 1;
       }
+    }
+    if (st && st->keep_trace) {
+      st->trace.push_back(best);
+      st->trace.push_back((int64_t)live_before);
+      st->trace.push_back(st->merges - merges_before);
     }
     T.swap(next);
   }
@@ -448,6 +458,19 @@ int64_t orc_encode(const void* h, int tier, const uint8_t* s, int64_t n, int32_t
   if (!ids.empty()) std::memcpy(out, ids.data(), ids.size() * sizeof(int32_t));
   if (stats) { stats[0] = st.passes; stats[1] = st.visits; stats[2] = st.merges; }
   return (int64_t)ids.size();
+}
+
+// What each pass of the pass view (tier 2) did on one string: trace receives, per pass, the rank applied, the
+// number of live tokens at the start of the pass and the number of merges the pass applied (3 values per pass, at
+// most `capacity` passes are written).  Returns the number of passes.
+int64_t orc_pass_trace(const void* h, const uint8_t* s, int64_t n, int64_t* trace, int64_t capacity) {
+  PassStats st;
+  st.keep_trace = true;
+  encode_passes(*(const Table*)h, s, n, &st);
+  const int64_t passes = (int64_t)st.trace.size() / 3;
+  for (int64_t i = 0; i < passes && i < capacity; ++i)
+    for (int k = 0; k < 3; ++k) trace[3 * i + k] = st.trace[(size_t)(3 * i + k)];
+  return passes;
 }
 
 // Encode a batch on `nthreads` host threads.  out_ids (capacity offsets[batch]) receives the dense

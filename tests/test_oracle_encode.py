@@ -145,6 +145,34 @@ def test_invariants_on_random_inputs():
             assert continue_encoding(rows, part) == ids
             assert t.encode(data, oracle.HEAP).tolist() == ids
             assert t.encode(data, oracle.PASSES).tolist() == ids
+            check_pass_invariants(t, data, len(ids))
+
+
+def check_pass_invariants(table, data, n_tokens):
+    """The one-rank-per-pass view (section 4.2) of a table whose rows only use older tokens: the rank applied
+    strictly increases from pass to pass, every pass applies at least one merge, and a pass that starts with
+    L live tokens and applies m merges leaves L - m."""
+    trace = table.pass_trace(data)
+    live = len(data)
+    last_rank = -1
+    for rank, live_before, merges in trace:
+        assert rank > last_rank, trace
+        assert live_before == live and merges >= 1
+        live -= merges
+        last_rank = rank
+    assert live == n_tokens
+
+
+def test_pass_trace_hand_worked():
+    """'abcabcabc' with rows ab, bc, (ab)c, (abc)(abc): rank 0 three times, rank 2 three times, rank 3 once (row 1,
+    'bc', never applies: its b is taken by 'ab' first)."""
+    t = oracle.Table([(97, 98), (98, 99), (256, 99), (258, 258)])
+    assert t.pass_trace("abcabcabc") == [(0, 9, 3), (2, 6, 3), (3, 3, 1)]
+    assert t.pass_trace("") == [] and t.pass_trace("zzz") == []
+    # a table that breaks the operand-order rule is where the pass view leaves Algorithm 1: the invariant is
+    # a property of valid tables, not of the code (ranks go 1, then 0: not increasing)
+    bad = oracle.Table([(256 + 1, 99), (97, 98)])
+    assert [r for r, _, _ in bad.pass_trace("abc")] == [1, 0]
 
 
 def continue_encoding(rows, toks):
