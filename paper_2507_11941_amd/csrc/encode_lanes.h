@@ -29,7 +29,6 @@ namespace bpe {
 constexpr int kLaneItemBytes = 1024;            // capacity of a work item
 constexpr int kLaneRows = kLaneItemBytes / 64;
 constexpr int kLaneSegmentMax = 32;             // positions a lane's liveness mask covers
-constexpr int kLanePad = 32;                    // words after the position arrays that a scan may read
 constexpr uint32_t kLaneChunk = 4;              // work items a workgroup claims at a time (1: 3.4 ms on the
                                                 // 270,000 pieces of the throughput workload, 2: 2.2, 4: 2.1, 8: 2.1)
 
@@ -45,14 +44,15 @@ __device__ inline uint32_t lane_merged_word(uint32_t lv) {
   return (256u + (lv >> kRankShift)) | ((lv & (kFlagLeft | kFlagRight)) << 20);
 }
 
-// Per-wave LDS, in 32-bit words.
+// Per-wave LDS, in 32-bit words.  (9.3 KB: sixteen workgroups per CU, four waves per SIMD.)
 struct LaneLds {
-  static constexpr int kT = 0;                                          // token word of every position
-  static constexpr int kV = kT + kLaneItemBytes + kLanePad;             // pair value of every position
-  static constexpr int kEnds = kV + kLaneItemBytes + kLanePad;          // bit p: position p ends its segment
-  static constexpr int kSeg = kEnds + kLaneItemBytes / 32 + 4;          // uint16: first position | (length - 1) << 10
-  static constexpr int kHist = kSeg + kLaneItemBytes / 4;               // segments of each length, then list bases
-  static constexpr int kWords = kHist + 32;
+  static constexpr int kFlags = 0;                                      // 2 bits per byte value: can be a left / right operand
+  static constexpr int kT = kFlags + 16;                                // token word of every position
+  static constexpr int kV = kT + kLaneItemBytes;                        // pair value of every position; a scan may
+  static constexpr int kEnds = kV + kLaneItemBytes;                     //   read up to 31 words on (masked out)
+  static constexpr int kSeg = kEnds + kLaneItemBytes / 32 + 4;          // bit p of kEnds: position p ends its segment
+  static constexpr int kHist = kSeg + kLaneItemBytes / 4;               // kSeg: uint16 first position | (length - 1) << 10
+  static constexpr int kWords = kHist + 32;                             // kHist: segments of each length, then list bases
 };
 
 __device__ inline uint32_t mbcnt64(uint64_t mask) {                     // set bits of mask below my lane
@@ -60,9 +60,9 @@ __device__ inline uint32_t mbcnt64(uint64_t mask) {                     // set b
 }
 
 // Encodes item s if all its segments fit a lane; returns false (and has written nothing to global memory) if
-// one does not.  lds: this wave's LaneLds words; byte_word: the 256 token words of the bytes, in LDS.
+// one does not.  lds: this wave's LaneLds words (kFlags filled in by the kernel).
 template <bool SPECIAL>
-__device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, const uint32_t* byte_word) {
+__device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds) {
   const int lane = (int)threadIdx.x & 63;
   const DeviceTable& tab = p.table;
   uint32_t* const T = lds + LaneLds::kT;
@@ -107,7 +107,8 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
         nb = lane == 63 ? wrap : nb;
         const bool has_pair = 64 * j + lane + 1 < n;
         if (has_pair) raw[j] = tab.byte_pair[(b[j] << 8) | nb];          // (the item's last byte ends a segment)
-        word[j] = byte_word[b[j]];
+        // token word of a byte: its value and the two capability bits (bits 30 and 31) from the packed table
+        word[j] = b[j] | (((lds[LaneLds::kFlags + (b[j] >> 4)] >> (2u * (b[j] & 15u))) & 3u) << 30);
         if constexpr (SPECIAL) {
           // an occurrence of a special token is one token on its first byte and nothing on the others; no
           // pair involves it, so there is a cut on both sides of every marked byte
@@ -306,14 +307,23 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds, c
 template <bool SPECIAL, bool INLINE>
 __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   extern __shared__ uint32_t smem[];
-  uint32_t* const byte_word = smem;                    // [256], then the per-item arrays
-  uint32_t* const arrays = smem + 256;
+  uint32_t* const arrays = smem;                       // this wave's LaneLds
   const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
   const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
   // items per claim: as many as keep every workgroup of the grid busy, kLaneChunk at most
   const uint32_t per_claim = min(kLaneChunk, max(1u, count / gridDim.x));
   if (blockIdx.x * per_claim >= count) return;         // uniform: nothing for this workgroup
-  for (int i = (int)threadIdx.x; i < 256; i += 64) byte_word[i] = p.table.byte_word[i];
+  // the capability bits of the 256 byte tokens, packed 16 bytes to a word
+  if (threadIdx.x < 16) arrays[LaneLds::kFlags + threadIdx.x] = 0;
+  __syncthreads();
+  {
+    uint32_t bits = 0;
+    for (int k = 0; k < 4; ++k) bits |= (p.table.byte_word[4 * threadIdx.x + k] >> 30) << (2 * k);
+    atomicOr(&arrays[LaneLds::kFlags + (threadIdx.x >> 2)], bits << (8 * (threadIdx.x & 3)));
+  }
+  uint32_t* const byte_word = smem + LaneLds::kWords;  // INLINE only: the byte token words for the other encoder
+  if constexpr (INLINE)
+    for (int i = (int)threadIdx.x; i < 256; i += 64) byte_word[i] = p.table.byte_word[i];
 
   // warm this XCD's L2 with the merge table (see encode_kernel)
   if (p.prefetch_lines > 0) {
@@ -325,7 +335,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
     uint32_t sink = 0;
     for (uint32_t line = lo + threadIdx.x; line < hi; line += 64)
       sink |= __builtin_nontemporal_load((const uint32_t*)p.table.buckets + (size_t)line * 32);
-    if (sink == 0x9E3779B9u && p.prefetch_lines == 0xFFFFFFFFu) byte_word[0] = sink;   // keeps the loads alive
+    if (sink == 0x9E3779B9u && p.prefetch_lines == 0xFFFFFFFFu) arrays[LaneLds::kHist] = sink;   // keeps the loads alive
   }
   __syncthreads();
 
@@ -336,19 +346,20 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   while (chunk * per_claim < count) {
     for (uint32_t item = chunk * per_claim; item < min((chunk + 1) * per_claim, count); ++item) {
       const int s = p.list ? (int)uniform((uint32_t)p.list[first + item]) : (int)item;
-      const bool done = encode_item_lanes<SPECIAL>(p, s, arrays, byte_word);
+      const bool done = encode_item_lanes<SPECIAL>(p, s, arrays);
       if (!done) {                                     // uniform
         if constexpr (INLINE) {
           __syncthreads();
           BlockShared<1> sh;
-          uint32_t* cur = arrays + 3 * kLaneItemBytes;
+          uint32_t* const other = byte_word + 256;     // the other encoder's arrays lie behind this one's
+          uint32_t* cur = other + 3 * kLaneItemBytes;
           sh.rec = (WaveRecord*)cur; cur += 2 * 8;
           sh.first_tok = cur; cur += 2;
           sh.part = cur; cur += 2;
           sh.item = cur;
           sh.byte_word = byte_word;
-          encode_string_segmented<1, 16, true, SPECIAL>(p, s, arrays, arrays + kLaneItemBytes,
-                                                        arrays + 2 * kLaneItemBytes, sh);
+          encode_string_segmented<1, 16, true, SPECIAL>(p, s, other, other + kLaneItemBytes,
+                                                        other + 2 * kLaneItemBytes, sh);
         } else {
           // every lane takes part in the atomic (lane 0 adds 1): no lane-dependent branch at the loop's edge
           const uint32_t slot = uniform(atomicAdd(p.fallback_count, threadIdx.x == 0 ? 1u : 0u));
@@ -364,9 +375,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
 
 template <bool INLINE>
 constexpr size_t lanes_lds_bytes() {
-  constexpr size_t own = 256 + LaneLds::kWords;
-  constexpr size_t with_fallback = 256 + 3 * kLaneItemBytes + 24;
-  return sizeof(uint32_t) * (INLINE && with_fallback > own ? with_fallback : own);
+  return sizeof(uint32_t) * (LaneLds::kWords + (INLINE ? 256 + 3 * kLaneItemBytes + 24 : 0));
 }
 
 }  // namespace bpe
