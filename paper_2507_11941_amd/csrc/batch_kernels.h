@@ -227,45 +227,55 @@ __global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offset
   }
 }
 
-// One wave per slot: where does its piece start?
+// Sixteen lanes per slot, four slots per wave: where does the slot's piece start?  The candidates are the 128
+// positions q = t, t-1, ..., t-127 below the slot's nominal start t (a cut "before q" lies between bytes q-1 and
+// q); the largest one with a cut wins.  A group looks at sixteen candidates per round -- in text the first round
+// nearly always finds one -- and the wave goes on while any of its groups is still looking.
+constexpr int kCutSlotsPerWave = 4;
 __global__ __launch_bounds__(256) void cut_search_kernel(const uint8_t* bytes, const int64_t* offsets,
                                                          const uint32_t* byte_pair, int piece_target,
                                                          int max_string, const Control* c, const int32_t* slot_base,
                                                          const int32_t* slot_string, int64_t* piece_begin,
                                                          const uint8_t* cover) {
-  const uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (g >= c->n_slots) return;
-  const int s = slot_string[g];
-  const int i = (int)g - slot_base[s];
-  const int64_t begin = offsets[s];
-  const int64_t len = offsets[s + 1] - begin;
+  const int lane = threadIdx.x & 63, sub = lane & 15, group = lane >> 4;
+  const uint32_t g = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kCutSlotsPerWave + group;
+  const bool valid = g < c->n_slots;
   int64_t start = -1;                                  // void unless a cut is found
-  if (len < 0 || len > max_string) {
-    start = -1;                                        // not encodable: the string yields no tokens
-  } else if (i == 0) {
-    start = begin;
-  } else {
-    // candidates q = t, t-1, ..., t-127 (a cut "before q" lies between bytes q-1 and q); lane l checks
-    // t-2l and t-2l-1.  piece_target >= 2 * kCutWindow keeps q-2 inside the string.
-    const int64_t t = begin + (int64_t)i * piece_target;
-    const int64_t q0 = t - 2 * lane;
-    const uint32_t a = bytes[q0 - 2], b = bytes[q0 - 1], cc = bytes[q0];
-    bool cut0 = byte_pair[(b << 8) | cc] == kCut;            // before q0
-    bool cut1 = byte_pair[(a << 8) | b] == kCut;             // before q0 - 1
-    if (cover) {                                             // special tokens: their ends are cuts, their inside is not
-      const uint32_t ma = cover[q0 - 2], mb = cover[q0 - 1], mc = cover[q0];
-      cut0 = (cut0 || mb != 0 || mc != 0) && mc != kCoverRest;
-      cut1 = (cut1 || ma != 0 || mb != 0) && mb != kCoverRest;
-    }
-    const uint64_t m0 = __ballot(cut0), m1 = __ballot(cut1);
-    const uint64_t any = m0 | m1;
-    if (any) {
-      const int l = __builtin_ctzll(any);                    // the lane with the largest candidates
-      start = (m0 >> l & 1) ? t - 2 * l : t - 2 * l - 1;
+  int64_t t = 0;
+  bool searching = false;
+  if (valid) {
+    const int s = slot_string[g];
+    const int i = (int)g - slot_base[s];
+    const int64_t begin = offsets[s];
+    const int64_t len = offsets[s + 1] - begin;
+    if (len < 0 || len > max_string) {
+      start = -1;                                      // not encodable: the string yields no tokens
+    } else if (i == 0) {
+      start = begin;
+    } else {
+      t = begin + (int64_t)i * piece_target;           // piece_target >= 2 * kCutWindow keeps q-1 inside the string
+      searching = true;
     }
   }
-  if (lane == 0) piece_begin[g] = start;
+  for (int round = 0; round < kCutWindow / 16; ++round) {
+    if (!__ballot(searching)) break;                   // uniform
+    bool cut = false;
+    if (searching) {
+      const int64_t q = t - 16 * round - sub;
+      const uint32_t a = bytes[q - 1], b = bytes[q];
+      cut = byte_pair[(a << 8) | b] == kCut;
+      if (cover) {                                     // special tokens: their ends are cuts, their inside is not
+        const uint32_t ma = cover[q - 1], mb = cover[q];
+        cut = (cut || ma != 0 || mb != 0) && mb != kCoverRest;
+      }
+    }
+    const uint32_t mine = (uint32_t)(__ballot(cut) >> (16 * group)) & 0xFFFFu;
+    if (searching && mine) {
+      start = t - 16 * round - __builtin_ctz(mine);    // the largest candidate of the round
+      searching = false;
+    }
+  }
+  if (valid && sub == 0) piece_begin[g] = start;
 }
 
 // One thread per slot: piece lengths, and the histogram of (tier, length bucket) keys.
@@ -459,20 +469,39 @@ __global__ __launch_bounds__(256) void special_mark_kernel(const uint8_t* bytes,
   }
 }
 
-// One wave per slot: copy the piece's ids to their place in the dense output.  (A piece has a few hundred ids;
-// what limits this kernel is the number of pieces whose descriptor loads are in flight, so waves, not
-// workgroups, take the pieces.)
+// Copy every piece's ids to their place in the dense output.  A piece has a few hundred ids, so what limits
+// this kernel is how many loads are in flight: a wave takes several pieces, reads the next piece's descriptor
+// while it copies the current one, and issues four rows of loads before the first store.
 __global__ __launch_bounds__(256) void piece_pack_kernel(const int32_t* tmp_ids, const Control* c,
                                                          const int64_t* piece_begin, const int32_t* counts,
                                                          const int64_t* slot_out, int32_t* out_ids,
                                                          const int32_t* id_map) {
   const uint32_t n_slots = c->n_slots;
   const int lane = threadIdx.x & 63;
-  for (uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6); g < n_slots; g += gridDim.x * 4) {
-    const int k = counts[g];
-    if (k <= 0) continue;
-    const int64_t src = piece_begin[g], dst = slot_out[g];
-    for (int i = lane; i < k; i += 64) out_ids[dst + i] = vocabulary_id(id_map, tmp_ids[src + i]);
+  const uint32_t stride = gridDim.x * 4;
+  uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int k = 0;
+  int64_t src = 0, dst = 0;
+  if (g < n_slots) { k = counts[g]; src = piece_begin[g]; dst = slot_out[g]; }
+  while (g < n_slots) {
+    const uint32_t g_next = g + stride;
+    int k_next = 0;
+    int64_t src_next = 0, dst_next = 0;
+    if (g_next < n_slots) { k_next = counts[g_next]; src_next = piece_begin[g_next]; dst_next = slot_out[g_next]; }
+    for (int i0 = 0; i0 < k; i0 += 256) {
+      int32_t v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + 64 * u + lane;
+        v[u] = i < k ? tmp_ids[src + i] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + 64 * u + lane;
+        if (i < k) out_ids[dst + i] = vocabulary_id(id_map, v[u]);
+      }
+    }
+    g = g_next; k = k_next; src = src_next; dst = dst_next;
   }
 }
 

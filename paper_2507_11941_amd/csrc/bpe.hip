@@ -560,7 +560,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
       const int per_slot_grid = (int)std::min<int64_t>((w.max_slots + 255) / 256, 65536);
       hipLaunchKernelGGL(slot_layout_kernel, dim3((unsigned)((batch + 1023) / 1024)), dim3(1024), 0, stream, offsets, batch, kPieceTarget,
                          BPE_MAX_STRING_BYTES, ctrl, sb, ss);
-      hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 3) / 4)), dim3(256), 0, stream, bytes,
+      hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 4 * kCutSlotsPerWave - 1) / (4 * kCutSlotsPerWave))), dim3(256), 0, stream, bytes,
                          offsets, byte_pair, kPieceTarget, BPE_MAX_STRING_BYTES, ctrl, sb, ss, pb, cover);
       hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
                          pb, pl, counts);
@@ -651,7 +651,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
     hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(64), 0, stream, tile_sum, w.n_tiles, ctrl, out_offsets, batch);
     hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
                        slot_string, slot_out, out_offsets);
-    const int grid = (int)std::min<int64_t>((w.max_slots + 3) / 4, 262144);
+    const int grid = (int)std::min<int64_t>((w.max_slots + 3) / 4, 16384);   // 256 CUs x 8 workgroups x 8 rounds
     hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
                        slot_out, out_ids, table->d_id_map);
   }
