@@ -274,6 +274,11 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds) {
           x1 = t0[pl];
           y1 = word;
         }
+        if (!(after | lower)) {                                    // the merged token is all that is left of the
+          dead = 0xFFFFFFFFu;                                      // segment (two segments in three end like this):
+          pending = false;                                         // finished, without a trip that finds no pair
+          hold = 0;
+        }
       }
       probe_start(tab, x1, y1, pending_left, f1);
       probe_start(tab, x2, y2, merge, f2);
