@@ -49,11 +49,18 @@ __device__ inline int bin_key(int len, const TierPlan& plan) {
   return -1;                                         // longer than any launched variant: skipped
 }
 
+// What a work item is, stored beside its place in the work list: all that an encode kernel needs to start on it.
+struct ItemDesc {
+  int64_t begin;                                     // first byte of the item in `bytes`
+  int32_t len;                                       // its length in bytes
+  int32_t item;                                      // string index, or slot index when strings are split
+};
+
 // One workgroup bins the whole batch: histogram of (class, length bucket) keys in LDS, exclusive scan of the
 // 256 keys, then the scatter of string indices into the work list (class-major, longest bucket first).
 // Also resets the work-queue heads.  A second pass over the offsets is cheaper than a second launch.
 __global__ __launch_bounds__(1024) void bin_kernel(const int64_t* offsets, int batch, TierPlan plan, Control* c,
-                                                   int32_t* list, int32_t* counts) {
+                                                   int32_t* list, ItemDesc* desc, int32_t* counts) {
   __shared__ uint32_t hist[kBinKeys], scan[kBinKeys], cursor[kBinKeys];
   const int t = threadIdx.x;
   if (t < kBinKeys) { hist[t] = 0; cursor[t] = 0; }
@@ -84,6 +91,7 @@ __global__ __launch_bounds__(1024) void bin_kernel(const int64_t* offsets, int b
     if (key < 0) continue;
     const uint32_t pos = (scan[key] - hist[key]) + atomicAdd(&cursor[key], 1u);
     list[pos] = s;
+    desc[pos] = ItemDesc{offsets[s], (int32_t)len, s};
   }
 }
 
@@ -328,7 +336,7 @@ __global__ __launch_bounds__(256) void piece_scan_kernel(Control* c, int n_tiers
 // long text all have about the same length, hence the same key: a workgroup first ranks its pieces per key in
 // LDS and then reserves each key's range of the list with one global atomic.
 __global__ __launch_bounds__(256) void piece_scatter_kernel(TierPlan plan, Control* c, const int64_t* piece_begin,
-                                                            const int32_t* piece_len, int32_t* list) {
+                                                            const int32_t* piece_len, int32_t* list, ItemDesc* desc) {
   __shared__ uint32_t local[kBinKeys];                 // 256 threads, 256 keys
   local[threadIdx.x] = 0;
   __syncthreads();
@@ -344,7 +352,10 @@ __global__ __launch_bounds__(256) void piece_scatter_kernel(TierPlan plan, Contr
   __syncthreads();
   if (mine) local[threadIdx.x] = c->key_base[threadIdx.x] + atomicAdd(&c->cursor[threadIdx.x], mine);
   __syncthreads();
-  if (key >= 0) list[local[key] + rank] = (int32_t)g;
+  if (key >= 0) {
+    list[local[key] + rank] = (int32_t)g;
+    desc[local[key] + rank] = ItemDesc{piece_begin[g], piece_len[g], (int32_t)g};
+  }
 }
 
 // Token offsets of the slots: per-tile sums, scan of the tile sums, then the scan inside each tile.

@@ -171,7 +171,7 @@ struct WorkspaceLayout {
   bool split;                        // strings are cut into pieces
   int64_t max_slots;                 // upper bound on the number of work items (strings or piece slots)
   int n_tiles;                       // scan tiles over the slots
-  size_t control, list, fallback, counts, tmp_ids, cover, staged;
+  size_t control, list, list_desc, fallback, counts, tmp_ids, cover, staged;
   size_t slot_base, slot_string, piece_begin, piece_len, slot_out, tile_sum;   // split only
   size_t total;
 };
@@ -184,6 +184,7 @@ WorkspaceLayout layout_for(int32_t batch, int64_t total_bytes, int32_t max_len) 
   size_t at = 0;
   w.control = at; at += align_up(sizeof(Control));
   w.list = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
+  w.list_desc = at; at += align_up((size_t)w.max_slots * sizeof(ItemDesc));
   w.fallback = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.counts = at; at += align_up((size_t)w.max_slots * sizeof(int32_t));
   w.tmp_ids = at; at += align_up((size_t)total_bytes * sizeof(int32_t));
@@ -549,7 +550,8 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
     if (direct) {
       list = nullptr;
     } else if (!w.split) {
-      hipLaunchKernelGGL(bin_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, plan, ctrl, list, counts);
+      hipLaunchKernelGGL(bin_kernel, dim3(1), dim3(1024), 0, stream, offsets, batch, plan, ctrl, list,
+                         (ItemDesc*)(ws + w.list_desc), counts);
     } else {
       int32_t* sb = (int32_t*)(ws + w.slot_base);
       int32_t* ss = (int32_t*)(ws + w.slot_string);
@@ -566,7 +568,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
                          pb, pl, counts);
       hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
       hipLaunchKernelGGL(piece_scatter_kernel, dim3((unsigned)((w.max_slots + 255) / 256)), dim3(256), 0, stream, plan,
-                         ctrl, pb, pl, list);
+                         ctrl, pb, pl, list, (ItemDesc*)(ws + w.list_desc));
       piece_begin = pb;
       piece_len = pl;
       slot_base = sb;
@@ -583,6 +585,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
     p.piece_begin = piece_begin;
     p.piece_len = piece_len;
     p.list = list;
+    p.list_desc = list ? (const void*)(ws + w.list_desc) : nullptr;
     p.tier_base = ctrl->tier_base;
     p.queue_head = ctrl->queue_head;
     p.tmp_ids = tmp_ids;

@@ -57,6 +57,7 @@ struct EncodeParams {
   uint32_t* queue_head;       // [tiers] next unclaimed item of each tier
   int32_t* tmp_ids;           // ids of an item are written at tmp_ids[first byte of the item ...]
   int32_t* counts;            // token count of each item
+  const void* list_desc;      // ItemDesc of every entry of `list` (begin, length, item), in the same order
   uint32_t* staged;           // HBM staging for the variant whose strings exceed LDS (else null)
   uint32_t prefetch_lines;    // 128-byte lines of table memory to pull into L2 at kernel start (0 = none)
   uint32_t direct_count;      // when `list` is null: items are the strings 0..direct_count-1, one per workgroup

@@ -59,10 +59,11 @@ __device__ inline uint32_t mbcnt64(uint64_t mask) {                     // set b
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Encodes item s if all its segments fit a lane; returns false (and has written nothing to global memory) if
-// one does not.  lds: this wave's LaneLds words (kFlags filled in by the kernel).
+// Encodes item s -- n bytes from `begin` on (both uniform) -- if all its segments fit a lane; returns false (and
+// has written nothing to global memory) if one does not.  lds: this wave's LaneLds words (kFlags filled in by the
+// kernel).
 template <bool SPECIAL>
-__device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds) {
+__device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, int64_t begin, int n, uint32_t* lds) {
   const int lane = (int)threadIdx.x & 63;
   const DeviceTable& tab = p.table;
   uint32_t* const T = lds + LaneLds::kT;
@@ -71,8 +72,6 @@ __device__ bool encode_item_lanes(const EncodeParams& p, int s, uint32_t* lds) {
   uint16_t* const seg = (uint16_t*)(lds + LaneLds::kSeg);
   uint32_t* const hist = lds + LaneLds::kHist;
 
-  const int64_t begin = p.piece_begin ? p.piece_begin[s] : p.offsets[s];
-  const int n = (int)uniform((uint32_t)(p.piece_len ? p.piece_len[s] : (int32_t)(p.offsets[s + 1] - begin)));
   if (n <= 0 || n > kLaneItemBytes) {                  // uniform; too long only if max_len was wrong
     if (lane == 63) p.counts[s] = 0;
     return true;
@@ -346,22 +345,44 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
 
   // Items are claimed kLaneChunk at a time: the first chunk of a workgroup is its own index, later ones come from
   // the tier's queue head (which starts at zero).  One claim per item would make every wave wait for a round trip
-  // to the one contended address after each item.
-  uint32_t chunk = blockIdx.x;
-  while (chunk * per_claim < count) {
-    for (uint32_t item = chunk * per_claim; item < min((chunk + 1) * per_claim, count); ++item) {
-      const int s = p.list ? (int)uniform((uint32_t)p.list[first + item]) : (int)item;
-      const bool done = encode_item_lanes<SPECIAL>(p, s, arrays);
+  // to the one contended address after each item.  Lane i fetches the descriptor of the chunk's i-th item, so a
+  // chunk costs one round trip for its claim and one for its descriptors.  (Claiming ahead does not pay: loads
+  // return in order, so whatever is loaded after the claim waits for it.)
+  const int lane = (int)threadIdx.x & 63;
+  const ItemDesc* const descs = (const ItemDesc*)p.list_desc;
+  auto load_chunk = [&](uint64_t chunk, ItemDesc& d) {
+    d.begin = 0;
+    d.len = 0;
+    d.item = 0;
+    const uint64_t item = chunk * per_claim + (uint32_t)lane;
+    if ((uint32_t)lane < per_claim && item < count) {
+      if (descs) {
+        d = descs[first + item];
+      } else {                                         // no work list: item i is string i
+        d.begin = p.offsets[item];
+        d.len = (int32_t)(p.offsets[item + 1] - d.begin);
+        d.item = (int32_t)item;
+      }
+    }
+  };
+  auto encode_chunk = [&](uint64_t chunk, const ItemDesc& cur) __attribute__((always_inline)) {
+    const uint32_t here = (uint32_t)min((uint64_t)per_claim, count - chunk * per_claim);
+    for (uint32_t i = 0; i < here; ++i) {
+      const int s = __builtin_amdgcn_readlane(cur.item, (int)i);
+      const int n = __builtin_amdgcn_readlane(cur.len, (int)i);
+      const int64_t begin = ((int64_t)__builtin_amdgcn_readlane((int)(cur.begin >> 32), (int)i) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)cur.begin, (int)i);
+      const bool done = encode_item_lanes<SPECIAL>(p, s, begin, n, arrays);
       if (!done) {                                     // uniform
         if constexpr (INLINE) {
           __syncthreads();
           BlockShared<1> sh;
           uint32_t* const other = byte_word + 256;     // the other encoder's arrays lie behind this one's
-          uint32_t* cur = other + 3 * kLaneItemBytes;
-          sh.rec = (WaveRecord*)cur; cur += 2 * 8;
-          sh.first_tok = cur; cur += 2;
-          sh.part = cur; cur += 2;
-          sh.item = cur;
+          uint32_t* cur_word = other + 3 * kLaneItemBytes;
+          sh.rec = (WaveRecord*)cur_word; cur_word += 2 * 8;
+          sh.first_tok = cur_word; cur_word += 2;
+          sh.part = cur_word; cur_word += 2;
+          sh.item = cur_word;
           sh.byte_word = byte_word;
           encode_string_segmented<1, 16, true, SPECIAL>(p, s, other, other + kLaneItemBytes,
                                                         other + 2 * kLaneItemBytes, sh);
@@ -372,9 +393,18 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
         }
       }
     }
-    if (gridDim.x * per_claim >= count) break;         // uniform: the grid's own chunks cover the list
+  };
+  uint64_t chunk = blockIdx.x;
+  ItemDesc cur;
+  load_chunk(chunk, cur);
+  for (;;) {
+    encode_chunk(chunk, cur);
+    if ((uint64_t)gridDim.x * per_claim >= count) break;           // uniform: the grid's own chunks cover the list
+    // (lane 0 adds 1; every lane takes part, so that no lane-dependent branch sits at the loop's edge)
     const uint32_t claimed = atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
-    chunk = gridDim.x + uniform(claimed);              // lane 0's value, as a scalar
+    chunk = (uint64_t)gridDim.x + uniform(claimed);
+    if (chunk * per_claim >= count) break;             // uniform
+    load_chunk(chunk, cur);
   }
 }
 
