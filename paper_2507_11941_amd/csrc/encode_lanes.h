@@ -328,19 +328,6 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   uint32_t* const byte_word = smem + LaneLds::kWords;  // INLINE only: the byte token words for the other encoder
   if constexpr (INLINE)
     for (int i = (int)threadIdx.x; i < 256; i += 64) byte_word[i] = p.table.byte_word[i];
-
-  // warm this XCD's L2 with the merge table (see encode_kernel)
-  if (p.prefetch_lines > 0) {
-    constexpr uint32_t kXcds = 8;
-    const uint32_t peers = (gridDim.x + kXcds - 1) / kXcds;
-    const uint32_t me = blockIdx.x / kXcds;
-    const uint32_t per = (p.prefetch_lines + peers - 1) / peers;
-    const uint32_t lo = me * per, hi = min(lo + per, p.prefetch_lines);
-    uint32_t sink = 0;
-    for (uint32_t line = lo + threadIdx.x; line < hi; line += 64)
-      sink |= __builtin_nontemporal_load((const uint32_t*)p.table.buckets + (size_t)line * 32);
-    if (sink == 0x9E3779B9u && p.prefetch_lines == 0xFFFFFFFFu) arrays[LaneLds::kHist] = sink;   // keeps the loads alive
-  }
   __syncthreads();
 
   // Items are claimed kLaneChunk at a time: the first chunk of a workgroup is its own index, later ones come from
