@@ -173,9 +173,12 @@ __global__ __launch_bounds__(256) void pack_kernel(const int32_t* tmp_ids, const
 
 constexpr int kCutWindow = 128;
 
+__device__ inline uint32_t slots_of_length(int64_t len, int piece_target, int max_string) {
+  // (a 32-bit division: a valid length fits, and the 64-bit one is a long software routine)
+  return (len <= 0 || len > max_string) ? 1u : ((uint32_t)len + (uint32_t)piece_target - 1u) / (uint32_t)piece_target;
+}
 __device__ inline uint32_t slots_of(const int64_t* offsets, int s, int piece_target, int max_string) {
-  const int64_t len = offsets[s + 1] - offsets[s];
-  return (len <= 0 || len > max_string) ? 1u : (uint32_t)((len + piece_target - 1) / piece_target);
+  return slots_of_length(offsets[s + 1] - offsets[s], piece_target, max_string);
 }
 
 // Slots per string, their exclusive scan (slot_base), and the owner string of every slot.  Workgroup b owns
@@ -197,7 +200,18 @@ __global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offset
   }
   // slots of all strings before the tile
   uint32_t before = 0;
-  for (int s = tid; s < base; s += 1024) before += slots_of(offsets, s, piece_target, max_string);
+  for (int s0 = tid; s0 < base; s0 += 8 * 1024) {      // eight strings' loads in flight per thread: the loads
+    int64_t lo[8], hi[8];                              // are unconditional (index clamped), the test comes after
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = min(s0 + u * 1024, base - 1);
+      lo[u] = offsets[s];
+      hi[u] = offsets[s + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      before += s0 + u * 1024 < base ? slots_of_length(hi[u] - lo[u], piece_target, max_string) : 0u;
+  }
   for (int step = 32; step >= 1; step >>= 1) before += (uint32_t)__shfl_xor((int)before, step, 64);
   if (lane == 0) wave_sum[wave] = before;
   __syncthreads();
@@ -481,38 +495,55 @@ __global__ __launch_bounds__(256) void special_mark_kernel(const uint8_t* bytes,
 }
 
 // Copy every piece's ids to their place in the dense output.  A piece has a few hundred ids, so what limits
-// this kernel is how many loads are in flight: a wave takes several pieces, reads the next piece's descriptor
-// while it copies the current one, and issues four rows of loads before the first store.
+// this kernel is how many loads are in flight: a wave takes two pieces at a time, reads the next two descriptors
+// while it copies, and issues four rows of loads per piece before the first store.
+struct PackItem {
+  int k;
+  int64_t src, dst;
+};
+__device__ inline PackItem pack_item(uint32_t g, uint32_t n_slots, const int64_t* piece_begin, const int32_t* counts,
+                                     const int64_t* slot_out) {
+  PackItem it{0, 0, 0};
+  if (g < n_slots) {
+    it.k = counts[g];
+    it.src = piece_begin[g];
+    it.dst = slot_out[g];
+  }
+  return it;
+}
 __global__ __launch_bounds__(256) void piece_pack_kernel(const int32_t* tmp_ids, const Control* c,
                                                          const int64_t* piece_begin, const int32_t* counts,
                                                          const int64_t* slot_out, int32_t* out_ids,
                                                          const int32_t* id_map) {
   const uint32_t n_slots = c->n_slots;
   const int lane = threadIdx.x & 63;
-  const uint32_t stride = gridDim.x * 4;
+  const uint32_t stride = gridDim.x * 4;               // pieces one round of the grid takes: wave w takes w and w + stride
   uint32_t g = blockIdx.x * 4 + (threadIdx.x >> 6);
-  int k = 0;
-  int64_t src = 0, dst = 0;
-  if (g < n_slots) { k = counts[g]; src = piece_begin[g]; dst = slot_out[g]; }
+  PackItem a = pack_item(g, n_slots, piece_begin, counts, slot_out);
+  PackItem b = pack_item(g + stride, n_slots, piece_begin, counts, slot_out);
   while (g < n_slots) {
-    const uint32_t g_next = g + stride;
-    int k_next = 0;
-    int64_t src_next = 0, dst_next = 0;
-    if (g_next < n_slots) { k_next = counts[g_next]; src_next = piece_begin[g_next]; dst_next = slot_out[g_next]; }
-    for (int i0 = 0; i0 < k; i0 += 256) {
-      int32_t v[4];
+    const uint32_t g_next = g + 2 * stride;
+    const PackItem a_next = pack_item(g_next, n_slots, piece_begin, counts, slot_out);
+    const PackItem b_next = pack_item(g_next + stride, n_slots, piece_begin, counts, slot_out);
+    const int longest = max(a.k, b.k);                 // (per wave: uniform)
+    for (int i0 = 0; i0 < longest; i0 += 256) {
+      int32_t va[4], vb[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int i = i0 + 64 * u + lane;
-        v[u] = i < k ? tmp_ids[src + i] : 0;
+        va[u] = i < a.k ? tmp_ids[a.src + i] : 0;
+        vb[u] = i < b.k ? tmp_ids[b.src + i] : 0;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int i = i0 + 64 * u + lane;
-        if (i < k) out_ids[dst + i] = vocabulary_id(id_map, v[u]);
+        if (i < a.k) out_ids[a.dst + i] = vocabulary_id(id_map, va[u]);
+        if (i < b.k) out_ids[b.dst + i] = vocabulary_id(id_map, vb[u]);
       }
     }
-    g = g_next; k = k_next; src = src_next; dst = dst_next;
+    g = g_next;
+    a = a_next;
+    b = b_next;
   }
 }
 

@@ -654,7 +654,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
     hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(64), 0, stream, tile_sum, w.n_tiles, ctrl, out_offsets, batch);
     hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
                        slot_string, slot_out, out_offsets);
-    const int grid = (int)std::min<int64_t>((w.max_slots + 3) / 4, 16384);   // 256 CUs x 8 workgroups x 8 rounds
+    const int grid = (int)std::min<int64_t>((w.max_slots + 7) / 8, 8192);   // two pieces per wave and round
     hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
                        slot_out, out_ids, table->d_id_map);
   }
