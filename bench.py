@@ -276,6 +276,11 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": kernel_ms,
                      "kernel_calls_timed": kernel_calls},
     }
+    # the method's own look-up counts (section 4.2: every pair is looked up once, when it comes into being): the
+    # n - 1 initial byte pairs of a string go to the direct 256 x 256 table, and each of the n - k merges creates
+    # at most two pairs that go to the hash table
+    result["work"] = {"direct_table_lookups": w.total - w.batch, "merges": w.total - n_tokens,
+                      "hash_probes_upper_bound": 2 * (w.total - n_tokens)}
     if valu is not None and current:                     # how busy the vector ALUs are: the limit that applies
         rate = valu / (kernel_ms * 1e-3) / 1e9
         result["issue"] = {"bound": "alu", "achieved": rate, "peak": VALU_PEAK_GIPS, "unit": "G wave-instr/s",
