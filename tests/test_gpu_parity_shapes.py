@@ -105,6 +105,22 @@ def test_partly_cut_strings_leave_void_slots(bpe):
     check(bpe, rows, data, off, "void slots")
 
 
+def test_the_only_cut_at_every_distance_before_a_piece_boundary(bpe):
+    """Runs of 'a' under a doubling table (no cut inside a run) with a single 'b' -- the only place to cut --
+    placed so that the last cut before the piece boundary at byte 896 lies d bytes before it, for every d the
+    search window covers and a few beyond (then the slot is void and the piece runs on into a bigger variant)."""
+    a, b = ord("a"), ord("b")
+    rows = [(a, a)] + [(255 + j, 255 + j) for j in range(1, 10)]
+    strings = []
+    for d in list(range(0, 130)) + [200, 500]:
+        s = bytearray(b"a" * 1900)
+        s[896 - d - 1] = b                              # cuts before this byte and after it: the later one wins
+        strings.append(bytes(s))
+    strings.append(b"a" * 1900)                         # no cut at all
+    data, off = to_batch(strings)
+    check(bpe, rows, data, off, "cut distances", tier=oracle.TEXTBOOK)
+
+
 def test_table_where_every_bigram_is_a_cut(bpe):
     data, off = workloads.batch(3, batch_override=64)
     check(bpe, np.zeros((0, 2), dtype=np.int32), data, off, "empty table")
