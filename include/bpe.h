@@ -4,8 +4,10 @@
  * row index being the pair's rank -- Algorithm 1, "Require") and a batch of byte strings, return for every
  * string the token list T that Algorithm 1 ends with: start from the bytes, repeatedly replace the left-most
  * occurrence of the lowest-rank adjacent pair by its merged token, stop when no adjacent pair is in M.
- * Each string is encoded by one workgroup that loops over merge passes (section 4.2: look up pair ranks,
- * workgroup minimum, mark, write; section 4.3: one block per string).
+ * A string -- or, for a long string, a piece of it cut where no merge can cross -- is encoded by one workgroup
+ * (section 4.3: one block per string) that repeats section 4.2's steps (look up pair ranks, take the minimum,
+ * merge, look up the new pairs) until no pair is left, independently for every stretch of the string that no
+ * merge can leave.
  *
  * Token ids: a byte b is token b (byte-level pre-tokenisation, section 4.1); the token created by row r is
  * 256 + r.  Results are exact integers; there is nothing approximate in this interface.
