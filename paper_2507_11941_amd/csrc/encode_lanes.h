@@ -397,7 +397,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
 
 template <bool INLINE>
 constexpr size_t lanes_lds_bytes() {
-  return sizeof(uint32_t) * (LaneLds::kWords + (INLINE ? 256 + 3 * kLaneItemBytes + 24 : 0));
+  return lds_blocks(sizeof(uint32_t) * (LaneLds::kWords + (INLINE ? 256 + 3 * kLaneItemBytes + 24 : 0)));
 }
 
 }  // namespace bpe
