@@ -316,7 +316,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
   // items per claim: as many as keep every workgroup of the grid busy, kLaneChunk at most
   const uint32_t per_claim = min(kLaneChunk, max(1u, count / gridDim.x));
-  if (blockIdx.x * per_claim >= count) return;         // uniform: nothing for this workgroup
+  if ((uint64_t)blockIdx.x * per_claim >= count) return;   // uniform: nothing for this workgroup
   // the capability bits of the 256 byte tokens, packed 16 bytes to a word
   if (threadIdx.x < 16) arrays[LaneLds::kFlags + threadIdx.x] = 0;
   __syncthreads();
@@ -337,12 +337,12 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   // return in order, so whatever is loaded after the claim waits for it.)
   const int lane = (int)threadIdx.x & 63;
   const ItemDesc* const descs = (const ItemDesc*)p.list_desc;
-  auto load_chunk = [&](uint64_t chunk, ItemDesc& d) {
+  auto load_chunk = [&](uint64_t first_item, uint32_t n_items, ItemDesc& d) {
     d.begin = 0;
     d.len = 0;
     d.item = 0;
-    const uint64_t item = chunk * per_claim + (uint32_t)lane;
-    if ((uint32_t)lane < per_claim && item < count) {
+    const uint64_t item = first_item + (uint32_t)lane;
+    if ((uint32_t)lane < n_items) {
       if (descs) {
         d = descs[first + item];
       } else {                                         // no work list: item i is string i
@@ -352,8 +352,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
       }
     }
   };
-  auto encode_chunk = [&](uint64_t chunk, const ItemDesc& cur) __attribute__((always_inline)) {
-    const uint32_t here = (uint32_t)min((uint64_t)per_claim, count - chunk * per_claim);
+  auto encode_chunk = [&](uint32_t here, const ItemDesc& cur) __attribute__((always_inline)) {
     for (uint32_t i = 0; i < here; ++i) {
       const int s = __builtin_amdgcn_readlane(cur.item, (int)i);
       const int n = __builtin_amdgcn_readlane(cur.len, (int)i);
@@ -381,17 +380,27 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
       }
     }
   };
-  uint64_t chunk = blockIdx.x;
+  // A workgroup's own first chunk: per_claim items, and when the list is long zero to three more, by block index,
+  // so that the workgroups do not all come back for their first claim at the same moment (claims on one address
+  // are served one after the other, some ten nanoseconds each).
+  const uint32_t spread = per_claim == kLaneChunk ? 1u : 0u;
+  const uint32_t b = blockIdx.x, g = gridDim.x;
+  constexpr uint32_t kBefore[4] = {0, 0, 1, 3};        // extra items of the blocks before b within its group of four
+  uint64_t first_item = (uint64_t)b * per_claim + spread * ((b >> 2) * 6u + kBefore[b & 3u]);
+  const uint64_t own_items = (uint64_t)g * per_claim + spread * ((g >> 2) * 6u + kBefore[g & 3u]);
+  if (first_item >= count) return;                     // uniform
+  uint32_t here = (uint32_t)min((uint64_t)(per_claim + spread * (b & 3u)), count - first_item);
   ItemDesc cur;
-  load_chunk(chunk, cur);
+  load_chunk(first_item, here, cur);
   for (;;) {
-    encode_chunk(chunk, cur);
-    if ((uint64_t)gridDim.x * per_claim >= count) break;           // uniform: the grid's own chunks cover the list
+    encode_chunk(here, cur);
+    if (own_items >= count) break;                     // uniform: the grid's own chunks cover the list
     // (lane 0 adds 1; every lane takes part, so that no lane-dependent branch sits at the loop's edge)
     const uint32_t claimed = atomicAdd(p.queue_head + p.tier, threadIdx.x == 0 ? 1u : 0u);
-    chunk = (uint64_t)gridDim.x + uniform(claimed);
-    if (chunk * per_claim >= count) break;             // uniform
-    load_chunk(chunk, cur);
+    first_item = own_items + (uint64_t)uniform(claimed) * per_claim;
+    if (first_item >= count) break;                    // uniform
+    here = (uint32_t)min((uint64_t)per_claim, count - first_item);
+    load_chunk(first_item, here, cur);
   }
 }
 
