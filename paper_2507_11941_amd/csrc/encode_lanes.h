@@ -315,8 +315,12 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   const uint32_t first = p.list ? p.tier_base[p.tier] : 0u;
   const uint32_t count = p.list ? p.tier_base[p.tier + 1] - first : p.direct_count;
   // items per claim: as many as keep every workgroup of the grid busy, kLaneChunk at most
-  const uint32_t per_claim = min(kLaneChunk, max(1u, count / gridDim.x));
-  if ((uint64_t)blockIdx.x * per_claim >= count) return;   // uniform: nothing for this workgroup
+  // The workgroups that take part: as many as make the rounds even.  5,120 items on 4,096 resident workgroups
+  // are two rounds of 2,560 -- the same two item times, with fewer waves sharing each SIMD.
+  const uint32_t rounds = (count + gridDim.x - 1) / gridDim.x;
+  const uint32_t g = rounds ? (count + rounds - 1) / rounds : 1u;
+  const uint32_t per_claim = min(kLaneChunk, max(1u, count / g));
+  if (blockIdx.x >= g || (uint64_t)blockIdx.x * per_claim >= count) return;   // uniform: nothing for this workgroup
   // the capability bits of the 256 byte tokens, packed 16 bytes to a word
   if (threadIdx.x < 16) arrays[LaneLds::kFlags + threadIdx.x] = 0;
   __syncthreads();
@@ -384,7 +388,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   // so that the workgroups do not all come back for their first claim at the same moment (claims on one address
   // are served one after the other, some ten nanoseconds each).
   const uint32_t spread = per_claim == kLaneChunk ? 1u : 0u;
-  const uint32_t b = blockIdx.x, g = gridDim.x;
+  const uint32_t b = blockIdx.x;
   constexpr uint32_t kBefore[4] = {0, 0, 1, 3};        // extra items of the blocks before b within its group of four
   uint64_t first_item = (uint64_t)b * per_claim + spread * ((b >> 2) * 6u + kBefore[b & 3u]);
   const uint64_t own_items = (uint64_t)g * per_claim + spread * ((g >> 2) * 6u + kBefore[g & 3u]);
