@@ -372,6 +372,66 @@ __global__ __launch_bounds__(256) void piece_scatter_kernel(TierPlan plan, Contr
   }
 }
 
+// piece_hist_kernel, piece_scan_kernel and piece_scatter_kernel in one workgroup, for batches of at most
+// kSmallSlots slots (a launch costs more than the work of a small batch).  Thread t takes slots t, t + 1024, ...
+constexpr int kSmallSlots = 4096;
+__global__ __launch_bounds__(1024) void piece_list_small_kernel(const int64_t* offsets, TierPlan plan, Control* c,
+                                                                const int32_t* slot_base, const int32_t* slot_string,
+                                                                const int64_t* piece_begin, int32_t* piece_len,
+                                                                int32_t* counts, int32_t* list, ItemDesc* desc) {
+  __shared__ uint32_t hist[kBinKeys], scan[kBinKeys];
+  const int t = threadIdx.x;
+  if (t < kBinKeys) hist[t] = 0;
+  __syncthreads();
+  const uint32_t n_slots = c->n_slots;
+  constexpr int kPer = kSmallSlots / 1024;
+  int32_t len[kPer];
+  int key[kPer];
+  uint32_t rank[kPer];
+  int64_t start[kPer];
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    const uint32_t g = (uint32_t)t + 1024u * j;
+    len[j] = 0;
+    key[j] = -1;
+    rank[j] = 0;
+    start[j] = -1;
+    if (g < n_slots) {
+      start[j] = piece_begin[g];
+      if (start[j] >= 0) {
+        const int s = slot_string[g];
+        int64_t next = offsets[s + 1];
+        for (int h = (int)g + 1; h < slot_base[s + 1]; ++h)
+          if (piece_begin[h] >= 0) { next = piece_begin[h]; break; }
+        len[j] = (int32_t)(next - start[j]);
+        key[j] = bin_key(len[j], plan);
+        if (key[j] >= 0) rank[j] = atomicAdd(&hist[key[j]], 1u);
+      }
+      piece_len[g] = len[j];
+      if (key[j] < 0) counts[g] = 0;                   // void slot, or too long for the launched variants
+    }
+  }
+  __syncthreads();
+  if (t < kBinKeys) scan[t] = hist[t];
+  __syncthreads();
+  for (int step = 1; step < kBinKeys; step <<= 1) {    // inclusive scan, all threads reach the barriers
+    uint32_t v = 0;
+    if (t < kBinKeys && t >= step) v = scan[t - step];
+    __syncthreads();
+    if (t < kBinKeys) scan[t] += v;
+    __syncthreads();
+  }
+  if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : scan[(t <= plan.n_tiers ? t : plan.n_tiers) * kLenBuckets - 1];
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    if (key[j] >= 0) {
+      const uint32_t pos = scan[key[j]] - hist[key[j]] + rank[j];
+      list[pos] = (int32_t)((uint32_t)t + 1024u * j);
+      desc[pos] = ItemDesc{start[j], len[j], (int32_t)((uint32_t)t + 1024u * j)};
+    }
+  }
+}
+
 // Token offsets of the slots: per-tile sums, scan of the tile sums, then the scan inside each tile.
 constexpr int kScanTile = 4096;
 
@@ -446,6 +506,41 @@ __global__ __launch_bounds__(1024) void slot_offsets_kernel(const int32_t* count
     if (tid == 1023) carry_s = before + v;
     __syncthreads();
   }
+}
+
+// tile_sum_kernel, tile_scan_kernel and slot_offsets_kernel in one workgroup, for at most kSmallSlots slots.
+__global__ __launch_bounds__(1024) void slot_offsets_small_kernel(const int32_t* counts, const Control* c,
+                                                                  const int32_t* slot_base, const int32_t* slot_string,
+                                                                  int64_t* slot_out, int64_t* out_offsets, int batch) {
+  __shared__ int64_t wave_sum[16];
+  __shared__ int64_t carry_s;
+  const uint32_t n_slots = c->n_slots;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int j = 0; j < kSmallSlots / 1024; ++j) {
+    const uint32_t g = (uint32_t)j * 1024u + (uint32_t)tid;
+    const int64_t m = g < n_slots ? (int64_t)counts[g] : 0;
+    int64_t v = m;
+    for (int step = 1; step < 64; step <<= 1) {
+      const int64_t o = __shfl_up(v, step, 64);
+      if (lane >= step) v += o;
+    }
+    if (lane == 63) wave_sum[wave] = v;
+    __syncthreads();
+    int64_t before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    if (g < n_slots) {
+      const int64_t at = before + v - m;
+      slot_out[g] = at;
+      const int s = slot_string[g];
+      if ((uint32_t)slot_base[s] == g) out_offsets[s] = at;   // a string starts at its first slot
+    }
+    __syncthreads();
+    if (tid == 1023) carry_s = before + v;
+    __syncthreads();
+  }
+  if (tid == 0) out_offsets[batch] = carry_s;
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -564,11 +564,16 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
                          BPE_MAX_STRING_BYTES, ctrl, sb, ss);
       hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 4 * kCutSlotsPerWave - 1) / (4 * kCutSlotsPerWave))), dim3(256), 0, stream, bytes,
                          offsets, byte_pair, kPieceTarget, BPE_MAX_STRING_BYTES, ctrl, sb, ss, pb, cover);
-      hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
-                         pb, pl, counts);
-      hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
-      hipLaunchKernelGGL(piece_scatter_kernel, dim3((unsigned)((w.max_slots + 255) / 256)), dim3(256), 0, stream, plan,
-                         ctrl, pb, pl, list, (ItemDesc*)(ws + w.list_desc));
+      if (w.max_slots <= kSmallSlots) {
+        hipLaunchKernelGGL(piece_list_small_kernel, dim3(1), dim3(1024), 0, stream, offsets, plan, ctrl, sb, ss, pb, pl,
+                           counts, list, (ItemDesc*)(ws + w.list_desc));
+      } else {
+        hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
+                           pb, pl, counts);
+        hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
+        hipLaunchKernelGGL(piece_scatter_kernel, dim3((unsigned)((w.max_slots + 255) / 256)), dim3(256), 0, stream, plan,
+                           ctrl, pb, pl, list, (ItemDesc*)(ws + w.list_desc));
+      }
       piece_begin = pb;
       piece_len = pl;
       slot_base = sb;
@@ -650,10 +655,15 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
   } else {
     int64_t* tile_sum = (int64_t*)(ws + w.tile_sum);
     int64_t* slot_out = (int64_t*)(ws + w.slot_out);
-    hipLaunchKernelGGL(tile_sum_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum);
-    hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(64), 0, stream, tile_sum, w.n_tiles, ctrl, out_offsets, batch);
-    hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
-                       slot_string, slot_out, out_offsets);
+    if (w.max_slots <= kSmallSlots) {
+      hipLaunchKernelGGL(slot_offsets_small_kernel, dim3(1), dim3(1024), 0, stream, counts, ctrl, slot_base, slot_string,
+                         slot_out, out_offsets, batch);
+    } else {
+      hipLaunchKernelGGL(tile_sum_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum);
+      hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(64), 0, stream, tile_sum, w.n_tiles, ctrl, out_offsets, batch);
+      hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
+                         slot_string, slot_out, out_offsets);
+    }
     const int grid = (int)std::min<int64_t>((w.max_slots + 7) / 8, 8192);   // two pieces per wave and round
     hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
                        slot_out, out_ids, table->d_id_map);
