@@ -222,6 +222,31 @@ def encode_batch_static(table: Table, data, offsets, max_len: int, out_ids, out_
     return out_ids, out_offsets
 
 
+def encode_strings(table: Table, strings, device=None):
+    """Convenience for callers that start from host strings: ``strings`` is a sequence of ``bytes`` (or ``str``,
+    encoded as UTF-8); returns one int32 numpy array of token ids per string.  Marshalling only: the bytes are
+    joined, copied to the device, encoded by ``encode_batch`` and the ids copied back (this synchronises)."""
+    import numpy as np
+    import torch
+
+    raw = [s.encode("utf-8") if isinstance(s, str) else bytes(s) for s in strings]
+    lens = np.fromiter((len(b) for b in raw), dtype=np.int64, count=len(raw))
+    offsets = np.zeros(len(raw) + 1, dtype=np.int64)
+    np.cumsum(lens, out=offsets[1:])
+    max_len = int(lens.max()) if len(raw) else 0
+    if max_len > MAX_STRING_BYTES:
+        raise ValueError(f"a string has {max_len} bytes; the encoder takes at most {MAX_STRING_BYTES}")
+    dev = torch.device(device if device is not None else "cuda:0")
+    data = np.frombuffer(b"".join(raw), dtype=np.uint8)
+    d = torch.from_numpy(data.copy()).to(dev) if len(data) else torch.empty(0, dtype=torch.uint8, device=dev)
+    o = torch.from_numpy(offsets).to(dev)
+    with torch.cuda.device(dev):
+        ids, out_off = encode_batch(table, d, o, max_len)
+    out_off = out_off.cpu().numpy()
+    ids = ids[: int(out_off[-1])].cpu().numpy()
+    return [ids[out_off[i]:out_off[i + 1]] for i in range(len(raw))]
+
+
 def set_profiling(enabled: bool) -> None:
     _check(load_library().bpe_set_profiling(1 if enabled else 0), "bpe_set_profiling")
 

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
+import workloads
 from conftest import parse_ids, parse_rows, read_golden
 from gpu_util import assert_same_encoding, gpu_encode, to_batch
 
@@ -247,3 +248,20 @@ def test_random_texts_with_special_tokens(bpe):
         want_ids, want_off = orc.encode_batch(data, off, tier=oracle.HEAP, nthreads=8)
         assert_same_encoding(ids, out_off, want_ids, want_off, f"specials trial {trial}")
         table.free()
+
+
+def test_encode_strings_convenience(bpe):
+    """Host strings in, one id array per string out: str and bytes, empty strings, a string above 1 KiB."""
+    merges = workloads.load_merges("1k")
+    table = bpe.build_table(merges)
+    orc = oracle.Table(merges)
+    text = workloads.text(1, 77, 3000).tobytes()
+    strings = ["the quick brown fox", b"", text[:10], text[10:1500], "", text[1500:]]
+    got = bpe.encode_strings(table, strings)
+    assert len(got) == len(strings)
+    for s, ids in zip(strings, got):
+        raw = s.encode() if isinstance(s, str) else s
+        assert ids.tolist() == orc.encode(raw, oracle.TEXTBOOK).tolist()
+    assert bpe.encode_strings(table, []) == []
+    table.free()
+
