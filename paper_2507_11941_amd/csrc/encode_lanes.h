@@ -30,7 +30,8 @@ constexpr int kLaneItemBytes = 1024;            // capacity of a work item
 constexpr int kLaneRows = kLaneItemBytes / 64;
 constexpr int kLaneSegmentMax = 32;             // positions a lane's liveness mask covers
 constexpr uint32_t kLaneChunk = 4;              // work items a workgroup claims at a time (1: 3.4 ms on the
-                                                // 270,000 pieces of the throughput workload, 2: 2.2, 4: 2.1, 8: 2.1)
+                                                // 270,000 pieces of the throughput workload, 2: 2.2, 4: 2.1, 8: 2.1);
+                                                // twice as many when the list holds 32 or more items per workgroup
 
 // Pair values as the lanes keep them: the table's value (rank in bits 12..31, the two operand-capability flags
 // in bits 10 and 11) with the bits below cleared, so that a position can ride in them through the minimum.
@@ -319,7 +320,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   // are two rounds of 2,560 -- the same two item times, with fewer waves sharing each SIMD.
   const uint32_t rounds = (count + gridDim.x - 1) / gridDim.x;
   const uint32_t g = rounds ? (count + rounds - 1) / rounds : 1u;
-  const uint32_t per_claim = min(kLaneChunk, max(1u, count / g));
+  const uint32_t per_claim = min(count / g >= 32u ? 2u * kLaneChunk : kLaneChunk, max(1u, count / g));
   if (blockIdx.x >= g || (uint64_t)blockIdx.x * per_claim >= count) return;   // uniform: nothing for this workgroup
   // the capability bits of the 256 byte tokens, packed 16 bytes to a word
   if (threadIdx.x < 16) arrays[LaneLds::kFlags + threadIdx.x] = 0;
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(64) void encode_lanes_kernel(EncodeParams p) {
   // A workgroup's own first chunk: per_claim items, and when the list is long zero to three more, by block index,
   // so that the workgroups do not all come back for their first claim at the same moment (claims on one address
   // are served one after the other, some ten nanoseconds each).
-  const uint32_t spread = per_claim == kLaneChunk ? 1u : 0u;
+  const uint32_t spread = per_claim >= kLaneChunk ? 1u : 0u;
   const uint32_t b = blockIdx.x;
   constexpr uint32_t kBefore[4] = {0, 0, 1, 3};        // extra items of the blocks before b within its group of four
   uint64_t first_item = (uint64_t)b * per_claim + spread * ((b >> 2) * 6u + kBefore[b & 3u]);
