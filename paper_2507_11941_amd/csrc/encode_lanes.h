@@ -78,6 +78,7 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
     return true;
   }
   const int rows = (n + 63) >> 6;                      // uniform
+  __builtin_amdgcn_s_setprio(1);                       // (the load phase too is a chain of round trips)
 
   // ---- load: byte-level pre-tokenisation (section 4.1), the initial pair values, segment ends and starts ----
   uint32_t n_segments = 0;                             // segments with a pair to look at (uniform)
@@ -141,6 +142,7 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
   }
   __syncthreads();                                     // one wave: orders the LDS traffic of the phases
 
+  __builtin_amdgcn_s_setprio(0);
   // ---- list, sorted: longest segments first (counting sort over the 31 possible lengths) ----
   {
     constexpr int kRounds = kLaneItemBytes / 2 / 64;   // at most 512 segments of two bytes
@@ -231,6 +233,9 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
         }
       }
     }
+    // From here to the issue of the new look-ups a wave is on its way to its next memory round trip: it goes
+    // before the waves that are scanning or loading (measured: 1 % on the large workloads).
+    __builtin_amdgcn_s_setprio(2);
     if (__ballot(pending)) {                           // the two pairs my last merge created
       const uint32_t r1 = probe_finish(tab, f1), r2 = probe_finish(tab, f2);
       if (pending) {
@@ -284,6 +289,7 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
       probe_start(tab, x2, y2, merge, f2);
     }
     take_segments();                                   // lanes whose segment just ended go on at once
+    __builtin_amdgcn_s_setprio(0);
   }
   __syncthreads();
 
