@@ -78,7 +78,8 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
     return true;
   }
   const int rows = (n + 63) >> 6;                      // uniform
-  __builtin_amdgcn_s_setprio(1);                       // (the load phase too is a chain of round trips)
+  __builtin_amdgcn_s_setprio(3);                       // (the load phase too is a chain of round trips, and the
+                                                       // sooner its loads go out the better)
 
   // ---- load: byte-level pre-tokenisation (section 4.1), the initial pair values, segment ends and starts ----
   uint32_t n_segments = 0;                             // segments with a pair to look at (uniform)
