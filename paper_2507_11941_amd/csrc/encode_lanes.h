@@ -270,7 +270,6 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
         dead |= 1u << r;
         t0[k] = word;
         t0[r] = kTokNone;
-        v0[r] = kLaneNoPair;
         pk = k;
         hold = 1u << k;
         x2 = word;
