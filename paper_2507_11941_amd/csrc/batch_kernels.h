@@ -346,29 +346,52 @@ __global__ __launch_bounds__(256) void piece_scan_kernel(Control* c, int n_tiers
   if (t <= kMaxTiers) c->tier_base[t] = t == 0 ? 0 : scan[(t <= n_tiers ? t : n_tiers) * kLenBuckets - 1];
 }
 
-// One thread per slot: scatter the pieces into the work list, tier-major, longest bucket first.  Pieces of a
-// long text all have about the same length, hence the same key: a workgroup first ranks its pieces per key in
-// LDS and then reserves each key's range of the list with one global atomic.
+// Scatter the pieces into the work list, tier-major, longest bucket first.  Pieces of a long text all have about
+// the same length, hence the same key: a workgroup first ranks its pieces per key in LDS and then reserves each
+// key's range of the list with one global atomic.  Those atomics land on a handful of addresses and are served
+// one after the other, so a workgroup takes kScatterPer slots per thread: fewer workgroups, fewer atomics.
+constexpr int kScatterPer = 4;
 __global__ __launch_bounds__(256) void piece_scatter_kernel(TierPlan plan, Control* c, const int64_t* piece_begin,
                                                             const int32_t* piece_len, int32_t* list, ItemDesc* desc) {
   __shared__ uint32_t local[kBinKeys];                 // 256 threads, 256 keys
   local[threadIdx.x] = 0;
   __syncthreads();
-  const uint32_t g = blockIdx.x * 256 + threadIdx.x;
-  int key = -1;
-  uint32_t rank = 0;
-  if (g < c->n_slots && piece_begin[g] >= 0) {
-    key = bin_key(piece_len[g], plan);
-    if (key >= 0) rank = atomicAdd(&local[key], 1u);
+  const uint32_t n_slots = c->n_slots;
+  int key[kScatterPer];
+  uint32_t rank[kScatterPer];
+  int64_t begin[kScatterPer];
+  int32_t len[kScatterPer];
+#pragma unroll
+  for (int j = 0; j < kScatterPer; ++j) {
+    const uint32_t g = (blockIdx.x * kScatterPer + j) * 256 + threadIdx.x;
+    key[j] = -1;
+    rank[j] = 0;
+    begin[j] = -1;
+    len[j] = 0;
+    if (g < n_slots) {
+      begin[j] = piece_begin[g];
+      len[j] = piece_len[g];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kScatterPer; ++j) {
+    if (begin[j] >= 0) {
+      key[j] = bin_key(len[j], plan);
+      if (key[j] >= 0) rank[j] = atomicAdd(&local[key[j]], 1u);
+    }
   }
   __syncthreads();
   const uint32_t mine = local[threadIdx.x];
   __syncthreads();
   if (mine) local[threadIdx.x] = c->key_base[threadIdx.x] + atomicAdd(&c->cursor[threadIdx.x], mine);
   __syncthreads();
-  if (key >= 0) {
-    list[local[key] + rank] = (int32_t)g;
-    desc[local[key] + rank] = ItemDesc{piece_begin[g], piece_len[g], (int32_t)g};
+#pragma unroll
+  for (int j = 0; j < kScatterPer; ++j) {
+    if (key[j] >= 0) {
+      const uint32_t g = (blockIdx.x * kScatterPer + j) * 256 + threadIdx.x;
+      list[local[key[j]] + rank[j]] = (int32_t)g;
+      desc[local[key[j]] + rank[j]] = ItemDesc{begin[j], len[j], (int32_t)g};
+    }
   }
 }
 

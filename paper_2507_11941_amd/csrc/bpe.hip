@@ -559,7 +559,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
       int32_t* pl = (int32_t*)(ws + w.piece_len);
       const uint32_t* byte_pair =
           (const uint32_t*)((const char*)table->d_mem + table->bucket_bytes) + 256;
-      const int per_slot_grid = (int)std::min<int64_t>((w.max_slots + 255) / 256, 65536);
+      const int per_slot_grid = (int)std::min<int64_t>((w.max_slots + 255) / 256, 256);   // (each workgroup ends with a few global atomics)
       hipLaunchKernelGGL(slot_layout_kernel, dim3((unsigned)((batch + 1023) / 1024)), dim3(1024), 0, stream, offsets, batch, kPieceTarget,
                          BPE_MAX_STRING_BYTES, ctrl, sb, ss);
       hipLaunchKernelGGL(cut_search_kernel, dim3((unsigned)((w.max_slots + 4 * kCutSlotsPerWave - 1) / (4 * kCutSlotsPerWave))), dim3(256), 0, stream, bytes,
@@ -571,7 +571,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
         hipLaunchKernelGGL(piece_hist_kernel, dim3(per_slot_grid), dim3(256), 0, stream, offsets, plan, ctrl, sb, ss,
                            pb, pl, counts);
         hipLaunchKernelGGL(piece_scan_kernel, dim3(1), dim3(256), 0, stream, ctrl, plan.n_tiers);
-        hipLaunchKernelGGL(piece_scatter_kernel, dim3((unsigned)((w.max_slots + 255) / 256)), dim3(256), 0, stream, plan,
+        hipLaunchKernelGGL(piece_scatter_kernel, dim3((unsigned)((w.max_slots + 256 * kScatterPer - 1) / (256 * kScatterPer))), dim3(256), 0, stream, plan,
                            ctrl, pb, pl, list, (ItemDesc*)(ws + w.list_desc));
       }
       piece_begin = pb;
