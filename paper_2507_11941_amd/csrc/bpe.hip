@@ -664,7 +664,7 @@ static int encode_enqueue(const bpe_table* table, const uint8_t* bytes, const in
       hipLaunchKernelGGL(slot_offsets_kernel, dim3(w.n_tiles), dim3(1024), 0, stream, counts, ctrl, tile_sum, slot_base,
                          slot_string, slot_out, out_offsets);
     }
-    const int grid = (int)std::min<int64_t>((w.max_slots + 7) / 8, 8192);   // two pieces per wave and round
+    const int grid = (int)std::min<int64_t>((w.max_slots + 7) / 8, 32768);   // two pieces per wave and round
     hipLaunchKernelGGL(piece_pack_kernel, dim3(grid), dim3(256), 0, stream, tmp_ids, ctrl, piece_begin, counts,
                        slot_out, out_ids, table->d_id_map);
   }
