@@ -240,7 +240,8 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
     // From here to the issue of the new look-ups a wave is on its way to its next memory round trip: it goes
     // before the waves that are scanning or loading (measured: 1 % on the large workloads).
     __builtin_amdgcn_s_setprio(2);
-    if (__ballot(pending)) {                           // the two pairs my last merge created
+    {                                                  // the two pairs my last merge created (no "if any lane":
+                                                       // nearly every trip has one, and the branch costs more)
       const uint32_t r1 = probe_finish(tab, f1), r2 = probe_finish(tab, f2);
       if (pending) {
         const uint32_t here = lane_value(r2);
@@ -258,7 +259,7 @@ __device__ __forceinline__ bool encode_item_lanes(const EncodeParams& p, int s, 
     pending = merge;
     pending_left = false;
     hold = 0;
-    if (__ballot(merge)) {
+    {
       uint32_t x1 = 0, y1 = kTokNone, x2 = 0, y2 = kTokNone;
       if (merge) {
         const uint32_t k = best & 31u;
