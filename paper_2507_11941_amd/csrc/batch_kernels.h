@@ -249,9 +249,9 @@ __global__ __launch_bounds__(1024) void slot_layout_kernel(const int64_t* offset
   }
 }
 
-// Sixteen lanes per slot, four slots per wave: where does the slot's piece start?  The candidates are the 128
+// Eight lanes per slot, eight slots per wave: where does the slot's piece start?  The candidates are the 128
 // positions q = t, t-1, ..., t-127 below the slot's nominal start t (a cut "before q" lies between bytes q-1 and
-// q); the largest one with a cut wins.  A group looks at sixteen candidates per round -- in text the first round
+// q); the largest one with a cut wins.  A group looks at eight candidates per round -- in text the first round
 // nearly always finds one -- and the wave goes on while any of its groups is still looking.
 constexpr int kCutSlotsPerWave = 4;
 __global__ __launch_bounds__(256) void cut_search_kernel(const uint8_t* bytes, const int64_t* offsets,
